@@ -1,0 +1,174 @@
+/*
+ * dreamddp.h - C ABI of the MI355X (gfx950) library for one worker's per-iteration step of local SGD with
+ * partial synchronisation (PLSGD, Algorithm 1 and Definition 1 / Eq. (5) of the DreamDDP paper) and for the
+ * layer-to-iteration scheduling problem of its Sec. 3.3 (Eq. (8), Algorithm 2).
+ *
+ * One iteration r (0-based) of one worker, with slot = r mod H:
+ *
+ *     ddp_pack(slot)             gather the slot's layers (the fp32 copy that is synchronised) into a flat buffer
+ *     [network: the N-1 peers' flat buffers of the same layers arrive; here they are staged device buffers]
+ *     ddp_partial_average(slot)  mean over the N replicas in rank order; per-layer divergence and norm
+ *     ddp_unpack(slot)           scatter the mean back into the model (and refresh the bf16 model copy)
+ *     ddp_local_update()         fused SGD-momentum or AdamW step on every layer
+ *
+ * Conventions
+ *   - Every function returns a ddp_status (0 = success).  Nothing throws, aborts or prints.  After a failure
+ *     ddp_last_error() gives a message.  Arguments are validated on the host before any kernel is launched.
+ *   - "device pointer" = address in the HBM of the context's GPU; "host pointer" = ordinary memory.
+ *     All device memory passed in is owned by the caller and must stay valid while the context uses it.
+ *   - The four per-iteration calls only enqueue kernels on the caller's stream (a hipStream_t passed as
+ *     void*, NULL = the default stream).  They never allocate, free, copy to the host or synchronise.
+ *   - A context is not thread-safe; calls that share a context or device buffers must be ordered by the caller.
+ *   - Layers are numbered 0..L-1 from the input side (the paper's layer 1) to the output side (layer L);
+ *     the backward pass visits L-1, L-2, ..., 0.  Times are integer nanoseconds.
+ */
+#ifndef DREAMDDP_H
+#define DREAMDDP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ddp_ctx ddp_ctx; /* opaque: owns only derived device tables and a small reduction scratch */
+
+typedef enum {
+    DDP_OK = 0,
+    DDP_EINVAL = 1, /* bad argument value (NULL, out of range, duplicate layer, ...) */
+    DDP_ESHAPE = 2, /* sizes do not match what was registered */
+    DDP_EALIGN = 3, /* pointer alignment requirement violated */
+    DDP_ENOMEM = 4, /* allocation of the context's tables failed */
+    DDP_EHIP = 5,   /* a HIP runtime call failed (message holds hipGetErrorString) */
+    DDP_ESCHED = 6, /* schedule missing or inconsistent with the registered model */
+    DDP_ESTATE = 7  /* call made in the wrong order (e.g. pack before register) */
+} ddp_status;
+
+enum { DDP_F32 = 0, DDP_BF16 = 1 };
+enum { DDP_OPT_SGDM = 0, DDP_OPT_ADAMW = 1 };
+enum { DDP_MAX_REPLICAS = 64 };
+
+/* Schedule policies.
+ *   ENP          Example 1 (equal-number partition): consecutive groups of floor/ceil(L/H) layers in BP order,
+ *                the remainder going to the earliest sets.
+ *   ROUND_ROBIN  slot = layer mod H (non-contiguous sets; Definition 1 only needs disjoint subsets).
+ *   FULL         every layer in the last slot: local SGD with full synchronisation, Eq. (2).
+ *   EVERY        every layer in every slot: per-iteration model averaging.
+ *   OPT          exact minimiser of Eq. (8) over all cuts of the BP-ordered layer sequence into H consecutive,
+ *                possibly empty sets; ties -> lexicographically largest (|L_1|, |L_2|, ...).
+ *   ALG2         Algorithm 2: depth-first search pruned by Properties 1-3, argmin over its solution set
+ *                (first minimum in visiting order, assign-branch visited first). */
+enum {
+    DDP_SCHED_ENP = 0,
+    DDP_SCHED_ROUND_ROBIN = 1,
+    DDP_SCHED_FULL = 2,
+    DDP_SCHED_EVERY = 3,
+    DDP_SCHED_OPT = 4,
+    DDP_SCHED_ALG2 = 5
+};
+
+/* Sec. 3.3, Eq. (8)-(11), Algorithm 2.  CPU only: needs no context and no GPU.
+ *   t_fp_ns, t_bp_ns, t_comm_ns  host, [L], per-layer forward / backward / communication time, >= 0.
+ *                                t_fp_ns may be NULL (it is a constant of the objective); t_bp_ns and t_comm_ns
+ *                                may be NULL for ENP, ROUND_ROBIN, FULL, EVERY.
+ *   out_slot        host, [L]: slot of each layer (EVERY: all zero, meaningless).
+ *   out_set_ptr     host, [H+1], out_set_layers host, [L] ([L*H] for EVERY): CSR; the layers of slot s are
+ *                   out_set_layers[out_set_ptr[s] .. out_set_ptr[s+1]) in BP order (descending layer id).
+ *   out_cost_ns     host, nullable: Eq. (8) of the result (only for contiguous policies ENP, FULL, OPT, ALG2;
+ *                   -1 otherwise).
+ * Errors: DDP_EINVAL for L < 1, H < 1, unknown policy, NULL outputs, negative times, or time sums that
+ * would overflow int64. */
+int ddp_schedule(int policy, int L, int H, const int64_t *t_fp_ns, const int64_t *t_bp_ns, const int64_t *t_comm_ns,
+                 int32_t *out_slot, int32_t *out_set_ptr, int32_t *out_set_layers, int64_t *out_cost_ns);
+
+/* Eq. (8) of a given schedule (CSR as above).  Every set must be a run of consecutive layers in BP order and
+ * the sets must follow each other in BP order (a cut of L-1..0), else DDP_ESCHED.  Host pointers. */
+int ddp_schedule_cost(int L, int H, const int64_t *t_bp_ns, const int64_t *t_comm_ns, const int32_t *set_ptr,
+                      const int32_t *set_layers, int64_t *out_cost_ns);
+
+/* Size of Algorithm 2's solution set Omega for the instance (Sec. 3.3, complexity analysis).  Host pointers. */
+int ddp_schedule_alg2_solutions(int L, int H, const int64_t *t_bp_ns, const int64_t *t_comm_ns, int64_t *out_count);
+
+/* Context on GPU `device` (HIP ordinal).  The device must be the caller's current device in later calls. */
+int ddp_create(ddp_ctx **out, int device);
+int ddp_destroy(ddp_ctx *ctx);
+
+/* Tuning knobs, to be set before ddp_register_model / ddp_set_schedule (they shape the tables built there):
+ *   "update_chunk", "mean_chunk", "copy_chunk"  elements per workgroup (multiple of 1024, 1024..1048576)
+ *   "nontemporal"                               0/1: streaming cache hints on loads and stores
+ * Unknown names or bad values: DDP_EINVAL. */
+int ddp_set_option(ddp_ctx *ctx, const char *name, int64_t value);
+
+/* Describe the local replica (Algorithm 1 input w_0 and its optimizer state): T tensors, tensor t belongs
+ * to layer layer_of[t] (host, [T], non-decreasing, covering 0..L-1) and has numel[t] > 0 elements (host, [T]).
+ *   sync_ptr[t]    device fp32 [numel]: the copy that is averaged and updated (the parameters themselves, or
+ *                  the fp32 master weights when param_dtype is DDP_BF16)
+ *   model_ptr[t]   device bf16 [numel]: the model copy, rewritten by round-to-nearest-even whenever sync_ptr
+ *                  changes; required iff param_dtype == DDP_BF16 (model_ptr itself may be NULL for DDP_F32)
+ *   grad_ptr[t]    device [numel] of grad_dtype (DDP_F32 or DDP_BF16)
+ *   state0_ptr[t]  device fp32 [numel]: momentum buffer (SGD-m) or first moment (AdamW)
+ *   state1_ptr[t]  device fp32 [numel]: second moment; the array may be NULL if AdamW is never used
+ * The pointer arrays are host arrays of device pointers.  Tensors need only the alignment of their element
+ * type; tensors whose pointers are 16-byte aligned (8 for bf16) take the 128-bit path throughout.
+ * Re-registering replaces the previous model and drops the schedule. */
+int ddp_register_model(ddp_ctx *ctx, int L, int T, const int32_t *layer_of, const int64_t *numel, int param_dtype,
+                       int grad_dtype, void *const *sync_ptr, void *const *model_ptr, void *const *grad_ptr,
+                       void *const *state0_ptr, void *const *state1_ptr);
+
+/* Install the iteration -> layer-set mapping (Definition 1; output Psi* of Algorithm 2) as CSR host arrays in
+ * the layout ddp_schedule writes.  Builds the per-slot device offset tables: the flat buffer of a slot is the
+ * dense concatenation of its layers in the order listed, each layer's tensors in registration order.
+ * A layer may appear in several slots but only once per slot. */
+int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, const int32_t *set_layers);
+
+/* Introspection for callers and parity checks (host outputs). */
+int64_t ddp_slot_numel(const ddp_ctx *ctx, int slot);   /* elements in the slot's flat buffer; < 0 on error */
+int ddp_slot_num_layers(const ddp_ctx *ctx, int slot);  /* < 0 on error */
+int ddp_slot_num_tensors(const ddp_ctx *ctx, int slot); /* < 0 on error */
+/* out_tensor_ids[j], out_off[j]: j-th tensor in flat order and its first element's flat index;
+ * out_layer_ids[i], out_layer_begin[i] (+ out_layer_begin[n_layers] = total): layers in flat order.
+ * Any output may be NULL. */
+int ddp_slot_layout(const ddp_ctx *ctx, int slot, int32_t *out_tensor_ids, int64_t *out_off, int32_t *out_layer_ids,
+                    int64_t *out_layer_begin);
+
+/* Algorithm 1, the operand of the averaging: flat_local[off_t + i] = sync_t[i] for the slot's tensors.
+ *   flat_local  device fp32, >= ddp_slot_numel(slot) elements, 16-byte aligned. */
+int ddp_pack(ddp_ctx *ctx, int slot, float *flat_local, void *stream);
+
+/* Eq. (5), second case: flat_out[i] = (x_0[i] + x_1[i] + ... + x_{N-1}[i]) * (1.0f / N), added left to right in
+ * fp32 in global rank order, where x_{local_rank} = flat_local and the other x_k are peers[0..N-2] in rank
+ * order.  Bit-reproducible: the same inputs give the same bits on every worker.
+ *   peers        host array of N-1 device pointers (fp32, >= slot numel, 16-byte aligned); may be NULL if N == 1
+ *   flat_out     device fp32, may be the same buffer as flat_local (no other overlap allowed)
+ *   layer_stats  device double [2 * ddp_slot_num_layers(slot)], nullable.  For the i-th layer of the slot:
+ *                [2i]   Gamma^l = (1/N) sum_k sum_j (flat_out[j] - x_k[j])^2   (model divergence, Sec. 3.4),
+ *                [2i+1] sum_j flat_out[j]^2; differences in fp32, squares and sums in fp64, fixed order. */
+int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_local, const float *const *peers, int N,
+                        int local_rank, float *flat_out, double *layer_stats, void *stream);
+
+/* Algorithm 1, w_{r+1}^{k,l} = average: sync_t[i] = flat[off_t + i]; with a bf16 model copy also
+ * model_t[i] = bf16_rne(flat[off_t + i]).  flat: device fp32, 16-byte aligned. */
+int ddp_unpack(ddp_ctx *ctx, int slot, const float *flat, void *stream);
+
+/* Eq. (5), first case (Algorithm 1 "update model") with the optimizers of the paper's experiments.
+ * kind DDP_OPT_SGDM:  buf = momentum*buf + g;  p = p - lr*buf
+ * kind DDP_OPT_ADAMW: m = beta1*m + (1-beta1)*g;  v = beta2*v + ((1-beta2)*g)*g;  p = p*(1 - lr*weight_decay);
+ *                     p = p - (lr/(1-beta1^step)) * ( m / (sqrt(v)/sqrt(1-beta2^step) + eps) )
+ * step is 1-based.  Every product and sum is a separate fp32 operation; bf16 gradients are widened exactly;
+ * the bf16 model copy, if registered, is rewritten from the new p by round-to-nearest-even.
+ * Applies to every registered tensor. */
+typedef struct {
+    int32_t kind;
+    float lr, momentum, beta1, beta2, eps, weight_decay;
+    int64_t step;
+} ddp_opt;
+int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream);
+
+/* Message of the last failure on this context (ctx == NULL: last failure of ddp_create / ddp_schedule* in
+ * this thread).  Never NULL; valid until the next call on the same context / thread. */
+const char *ddp_last_error(const ddp_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DREAMDDP_H */

@@ -264,7 +264,10 @@ class Worker:
         h = self.hyper
         for t in range(len(self.p)):
             if self.optimizer == "sgdm":
-                sgdm(self.p[t], grads[t], self.s0[t], h["lr"], h["momentum"])
+                g = grads[t] if grads[t].dtype == np.float32 else bf16_widen(grads[t])   # widening is exact
+                sgdm(self.p[t], g, self.s0[t], h["lr"], h["momentum"])
+                if self.model is not None:
+                    self.model[t][...] = bf16_rne(self.p[t])
             else:
                 adamw(self.p[t], grads[t], self.s0[t], self.s1[t], None if self.model is None else self.model[t],
                       h["lr"], h["beta1"], h["beta2"], h["eps"], h["weight_decay"], step)

@@ -1,0 +1,440 @@
+// Host side of the library: context, model registration, per-slot offset tables, argument checks and the four
+// per-iteration entry points (Algorithm 1 of the paper, one worker).  Kernels live in ddp_kernels.hip.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "ddp_internal.h"
+
+namespace ddp {
+
+static thread_local std::string g_err;
+
+int fail(const ddp_ctx *ctx, int code, const std::string &msg) {
+    if (ctx)
+        ctx->err = msg;
+    else
+        g_err = msg;
+    return code;
+}
+
+static int hip_fail(const ddp_ctx *ctx, hipError_t e, const char *what) {
+    return fail(ctx, DDP_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+template <class T>
+static int upload(const ddp_ctx *ctx, const std::vector<T> &host, T **dev) {
+    *dev = nullptr;
+    if (host.empty()) return DDP_OK;
+    hipError_t e = hipMalloc((void **)dev, host.size() * sizeof(T));
+    if (e != hipSuccess) {
+        *dev = nullptr;
+        return fail(ctx, DDP_ENOMEM, std::string("hipMalloc of a table failed: ") + hipGetErrorString(e));
+    }
+    e = hipMemcpy(*dev, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipMemcpy of a table");
+    return DDP_OK;
+}
+
+static void free_slot(SlotTables &s) {
+    if (s.d_copy) (void)hipFree(s.d_copy);
+    if (s.d_mean) (void)hipFree(s.d_mean);
+    if (s.d_layer_chunk_ptr) (void)hipFree(s.d_layer_chunk_ptr);
+    s.d_copy = nullptr;
+    s.d_mean = nullptr;
+    s.d_layer_chunk_ptr = nullptr;
+}
+
+static void drop_schedule(ddp_ctx *c) {
+    for (auto &s : c->slots) free_slot(s);
+    c->slots.clear();
+    c->H = 0;
+    if (c->d_partials) (void)hipFree(c->d_partials);
+    c->d_partials = nullptr;
+    c->partials_cap = 0;
+}
+
+static void drop_model(ddp_ctx *c) {
+    drop_schedule(c);
+    if (c->d_tensors) (void)hipFree(c->d_tensors);
+    if (c->d_update) (void)hipFree(c->d_update);
+    c->d_tensors = nullptr;
+    c->d_update = nullptr;
+    c->n_update = 0;
+    c->registered = false;
+}
+
+static int check_device(const ddp_ctx *c, const char *who) {
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return hip_fail(c, e, "hipGetDevice");
+    if (cur != c->device)
+        return fail(c, DDP_ESTATE, std::string(who) + ": current device " + std::to_string(cur) + " is not the context's device " +
+                                       std::to_string(c->device));
+    return DDP_OK;
+}
+
+// Launchers hand back the hipError_t of the launch (0 = success).
+static int after_launch(const ddp_ctx *c, const char *who, int hip_rc) {
+    if (hip_rc == 0) return DDP_OK;
+    return fail(c, DDP_EHIP, std::string(who) + ": kernel launch failed: " + hipGetErrorString((hipError_t)hip_rc));
+}
+
+static bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+}  // namespace ddp
+
+using namespace ddp;
+
+extern "C" const char *ddp_last_error(const ddp_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+extern "C" int ddp_create(ddp_ctx **out, int device) {
+    if (!out) return fail(nullptr, DDP_EINVAL, "ddp_create: out is NULL");
+    *out = nullptr;
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "ddp_create: hipGetDeviceCount");
+    if (device < 0 || device >= n) return fail(nullptr, DDP_EINVAL, "ddp_create: no such device " + std::to_string(device));
+    e = hipSetDevice(device);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "ddp_create: hipSetDevice");
+    ddp_ctx *c = new (std::nothrow) ddp_ctx();
+    if (!c) return fail(nullptr, DDP_ENOMEM, "ddp_create: out of host memory");
+    c->device = device;
+    *out = c;
+    return DDP_OK;
+}
+
+extern "C" int ddp_destroy(ddp_ctx *ctx) {
+    if (!ctx) return DDP_OK;
+    drop_model(ctx);
+    delete ctx;
+    return DDP_OK;
+}
+
+extern "C" int ddp_set_option(ddp_ctx *ctx, const char *name, int64_t value) {
+    if (!ctx || !name) return fail(ctx, DDP_EINVAL, "ddp_set_option: NULL argument");
+    std::string k(name);
+    auto chunk_ok = [&](int64_t v) { return v >= 1024 && v <= 1048576 && v % 1024 == 0; };
+    if (k == "update_chunk" || k == "mean_chunk" || k == "copy_chunk") {
+        if (!chunk_ok(value)) return fail(ctx, DDP_EINVAL, "ddp_set_option: chunk must be a multiple of 1024 in [1024, 1048576]");
+        if (ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_set_option: chunk sizes must be set before ddp_register_model");
+        (k == "update_chunk" ? ctx->update_chunk : k == "mean_chunk" ? ctx->mean_chunk : ctx->copy_chunk) = value;
+        return DDP_OK;
+    }
+    if (k == "nontemporal") {
+        if (value != 0 && value != 1) return fail(ctx, DDP_EINVAL, "ddp_set_option: nontemporal is 0 or 1");
+        ctx->nontemporal = value != 0;
+        return DDP_OK;
+    }
+    return fail(ctx, DDP_EINVAL, "ddp_set_option: unknown option " + k);
+}
+
+extern "C" int ddp_register_model(ddp_ctx *ctx, int L, int T, const int32_t *layer_of, const int64_t *numel, int param_dtype,
+                                  int grad_dtype, void *const *sync_ptr, void *const *model_ptr, void *const *grad_ptr,
+                                  void *const *state0_ptr, void *const *state1_ptr) {
+    if (!ctx) return fail(nullptr, DDP_EINVAL, "ddp_register_model: ctx is NULL");
+    if (L < 1 || T < L) return fail(ctx, DDP_EINVAL, "ddp_register_model: need L >= 1 and T >= L");
+    if (!layer_of || !numel || !sync_ptr || !grad_ptr || !state0_ptr) return fail(ctx, DDP_EINVAL, "ddp_register_model: NULL array");
+    if (param_dtype != DDP_F32 && param_dtype != DDP_BF16) return fail(ctx, DDP_EINVAL, "ddp_register_model: bad param_dtype");
+    if (grad_dtype != DDP_F32 && grad_dtype != DDP_BF16) return fail(ctx, DDP_EINVAL, "ddp_register_model: bad grad_dtype");
+    if (param_dtype == DDP_BF16 && !model_ptr) return fail(ctx, DDP_EINVAL, "ddp_register_model: bf16 params need model_ptr");
+    int rc = check_device(ctx, "ddp_register_model");
+    if (rc != DDP_OK) return rc;
+
+    std::vector<TensorDesc> ts((size_t)T);
+    std::vector<int32_t> first((size_t)L + 1, 0);
+    const uintptr_t galign = grad_dtype == DDP_F32 ? 4 : 2;
+    for (int t = 0; t < T; ++t) {
+        const std::string tn = "tensor " + std::to_string(t);
+        if (layer_of[t] < 0 || layer_of[t] >= L) return fail(ctx, DDP_EINVAL, "ddp_register_model: " + tn + " has a layer id out of range");
+        if (t == 0 ? layer_of[t] != 0 : (layer_of[t] != layer_of[t - 1] && layer_of[t] != layer_of[t - 1] + 1))
+            return fail(ctx, DDP_EINVAL, "ddp_register_model: layer_of must be non-decreasing and cover 0..L-1 (" + tn + ")");
+        if (numel[t] <= 0) return fail(ctx, DDP_ESHAPE, "ddp_register_model: " + tn + " has numel <= 0");
+        if (!sync_ptr[t] || !grad_ptr[t] || !state0_ptr[t]) return fail(ctx, DDP_EINVAL, "ddp_register_model: " + tn + " has a NULL pointer");
+        if (param_dtype == DDP_BF16 && !model_ptr[t]) return fail(ctx, DDP_EINVAL, "ddp_register_model: " + tn + " lacks its bf16 model copy");
+        if (!aligned(sync_ptr[t], 4) || !aligned(state0_ptr[t], 4) || !aligned(grad_ptr[t], galign) ||
+            (state1_ptr && state1_ptr[t] && !aligned(state1_ptr[t], 4)) ||
+            (param_dtype == DDP_BF16 && !aligned(model_ptr[t], 2)))
+            return fail(ctx, DDP_EALIGN, "ddp_register_model: " + tn + " is not aligned to its element type");
+        TensorDesc &d = ts[(size_t)t];
+        d.sync = (float *)sync_ptr[t];
+        d.model = param_dtype == DDP_BF16 ? (uint16_t *)model_ptr[t] : nullptr;
+        d.grad = grad_ptr[t];
+        d.state0 = (float *)state0_ptr[t];
+        d.state1 = state1_ptr ? (float *)state1_ptr[t] : nullptr;
+        d.numel = numel[t];
+        first[(size_t)layer_of[t] + 1] = t + 1;
+    }
+    if (layer_of[T - 1] != L - 1) return fail(ctx, DDP_EINVAL, "ddp_register_model: layer_of does not reach L-1");
+    bool has1 = state1_ptr != nullptr;
+    if (has1)
+        for (int t = 0; t < T; ++t) has1 = has1 && state1_ptr[t] != nullptr;
+
+    drop_model(ctx);
+    ctx->L = L;
+    ctx->T = T;
+    ctx->param_dtype = param_dtype;
+    ctx->grad_dtype = grad_dtype;
+    ctx->has_state1 = has1;
+    ctx->layer_of.assign(layer_of, layer_of + T);
+    ctx->numel.assign(numel, numel + T);
+    ctx->tensors = ts;
+    ctx->layer_first_tensor = first;
+
+    // update table: every tensor cut into runs of update_chunk elements
+    std::vector<UpdateChunk> uc;
+    for (int t = 0; t < T; ++t)
+        for (int64_t b = 0; b < numel[t]; b += ctx->update_chunk) {
+            int64_t n = std::min<int64_t>(ctx->update_chunk, numel[t] - b);
+            uc.push_back({b, t, (int32_t)n});
+        }
+    rc = upload(ctx, ts, &ctx->d_tensors);
+    if (rc == DDP_OK) rc = upload(ctx, uc, &ctx->d_update);
+    if (rc != DDP_OK) {
+        drop_model(ctx);
+        return rc;
+    }
+    ctx->n_update = (int64_t)uc.size();
+    ctx->registered = true;
+    return DDP_OK;
+}
+
+extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, const int32_t *set_layers) {
+    if (!ctx) return fail(nullptr, DDP_EINVAL, "ddp_set_schedule: ctx is NULL");
+    if (!ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_set_schedule: no model registered");
+    if (H < 1 || !set_ptr || !set_layers) return fail(ctx, DDP_EINVAL, "ddp_set_schedule: bad argument");
+    if (set_ptr[0] != 0) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: set_ptr[0] must be 0");
+    int rc = check_device(ctx, "ddp_set_schedule");
+    if (rc != DDP_OK) return rc;
+    for (int s = 0; s < H; ++s) {
+        if (set_ptr[s + 1] < set_ptr[s]) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: set_ptr is not monotone");
+        std::vector<char> seen((size_t)ctx->L, 0);
+        for (int j = set_ptr[s]; j < set_ptr[s + 1]; ++j) {
+            int l = set_layers[j];
+            if (l < 0 || l >= ctx->L) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: layer id out of range in slot " + std::to_string(s));
+            if (seen[(size_t)l]) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: layer " + std::to_string(l) + " listed twice in slot " + std::to_string(s));
+            seen[(size_t)l] = 1;
+        }
+    }
+
+    drop_schedule(ctx);
+    std::vector<SlotTables> slots((size_t)H);
+    int64_t max_mean_chunks = 0;
+    for (int s = 0; s < H; ++s) {
+        SlotTables &st = slots[(size_t)s];
+        std::vector<CopyChunk> cc;
+        std::vector<MeanChunk> mc;
+        std::vector<int32_t> lcp;
+        int64_t off = 0;
+        for (int j = set_ptr[s]; j < set_ptr[s + 1]; ++j) {
+            const int l = set_layers[j];
+            st.layers.push_back(l);
+            st.layer_begin.push_back(off);
+            lcp.push_back((int32_t)mc.size());
+            const int64_t layer_start = off;
+            for (int t = ctx->layer_first_tensor[(size_t)l]; t < ctx->layer_first_tensor[(size_t)l + 1]; ++t) {
+                st.tensors.push_back(t);
+                st.tensor_off.push_back(off);
+                for (int64_t b = 0; b < ctx->numel[(size_t)t]; b += ctx->copy_chunk) {
+                    int64_t n = std::min<int64_t>(ctx->copy_chunk, ctx->numel[(size_t)t] - b);
+                    cc.push_back({b, off + b, t, (int32_t)n});
+                }
+                off += ctx->numel[(size_t)t];
+            }
+            // mean chunks: cut the layer's flat range at multiples of mean_chunk measured from a 4-element
+            // boundary, so that every chunk but the first starts 16-byte aligned
+            int64_t b = layer_start;
+            while (b < off) {
+                int64_t e = std::min<int64_t>(off, (b / 4) * 4 + ctx->mean_chunk);
+                mc.push_back({b, (int32_t)(e - b), (int32_t)(j - set_ptr[s])});
+                b = e;
+            }
+        }
+        st.layer_begin.push_back(off);
+        lcp.push_back((int32_t)mc.size());
+        st.numel = off;
+        st.n_copy = (int64_t)cc.size();
+        st.n_mean = (int64_t)mc.size();
+        max_mean_chunks = std::max(max_mean_chunks, st.n_mean);
+        rc = upload(ctx, cc, &st.d_copy);
+        if (rc == DDP_OK) rc = upload(ctx, mc, &st.d_mean);
+        if (rc == DDP_OK) rc = upload(ctx, lcp, &st.d_layer_chunk_ptr);
+        if (rc != DDP_OK) {
+            for (auto &x : slots) free_slot(x);
+            return rc;
+        }
+    }
+    if (max_mean_chunks > 0) {
+        hipError_t e = hipMalloc((void **)&ctx->d_partials, (size_t)max_mean_chunks * 2 * sizeof(double));
+        if (e != hipSuccess) {
+            ctx->d_partials = nullptr;
+            for (auto &x : slots) free_slot(x);
+            return fail(ctx, DDP_ENOMEM, std::string("ddp_set_schedule: hipMalloc of the reduction scratch failed: ") + hipGetErrorString(e));
+        }
+        ctx->partials_cap = max_mean_chunks;
+    }
+    ctx->slots = std::move(slots);
+    ctx->H = H;
+    return DDP_OK;
+}
+
+static const SlotTables *slot_of(const ddp_ctx *ctx, int slot, const char *who, int *rc) {
+    if (!ctx) {
+        *rc = fail(nullptr, DDP_EINVAL, std::string(who) + ": ctx is NULL");
+        return nullptr;
+    }
+    if (ctx->H == 0) {
+        *rc = fail(ctx, DDP_ESCHED, std::string(who) + ": no schedule installed");
+        return nullptr;
+    }
+    if (slot < 0 || slot >= ctx->H) {
+        *rc = fail(ctx, DDP_EINVAL, std::string(who) + ": slot out of range");
+        return nullptr;
+    }
+    *rc = DDP_OK;
+    return &ctx->slots[(size_t)slot];
+}
+
+extern "C" int64_t ddp_slot_numel(const ddp_ctx *ctx, int slot) {
+    int rc;
+    const SlotTables *s = slot_of(ctx, slot, "ddp_slot_numel", &rc);
+    return s ? s->numel : -(int64_t)rc;
+}
+
+extern "C" int ddp_slot_num_layers(const ddp_ctx *ctx, int slot) {
+    int rc;
+    const SlotTables *s = slot_of(ctx, slot, "ddp_slot_num_layers", &rc);
+    return s ? (int)s->layers.size() : -rc;
+}
+
+extern "C" int ddp_slot_num_tensors(const ddp_ctx *ctx, int slot) {
+    int rc;
+    const SlotTables *s = slot_of(ctx, slot, "ddp_slot_num_tensors", &rc);
+    return s ? (int)s->tensors.size() : -rc;
+}
+
+extern "C" int ddp_slot_layout(const ddp_ctx *ctx, int slot, int32_t *out_tensor_ids, int64_t *out_off, int32_t *out_layer_ids,
+                               int64_t *out_layer_begin) {
+    int rc;
+    const SlotTables *s = slot_of(ctx, slot, "ddp_slot_layout", &rc);
+    if (!s) return rc;
+    if (out_tensor_ids) std::memcpy(out_tensor_ids, s->tensors.data(), s->tensors.size() * sizeof(int32_t));
+    if (out_off) std::memcpy(out_off, s->tensor_off.data(), s->tensor_off.size() * sizeof(int64_t));
+    if (out_layer_ids) std::memcpy(out_layer_ids, s->layers.data(), s->layers.size() * sizeof(int32_t));
+    if (out_layer_begin) std::memcpy(out_layer_begin, s->layer_begin.data(), s->layer_begin.size() * sizeof(int64_t));
+    return DDP_OK;
+}
+
+static int check_flat(const ddp_ctx *ctx, const void *p, const char *who, const char *what) {
+    if (!p) return fail(ctx, DDP_EINVAL, std::string(who) + ": " + what + " is NULL");
+    if (!aligned(p, 16)) return fail(ctx, DDP_EALIGN, std::string(who) + ": " + what + " must be 16-byte aligned");
+    return DDP_OK;
+}
+
+extern "C" int ddp_pack(ddp_ctx *ctx, int slot, float *flat_local, void *stream) {
+    int rc;
+    const SlotTables *s = slot_of(ctx, slot, "ddp_pack", &rc);
+    if (!s) return rc;
+    if ((rc = check_device(ctx, "ddp_pack")) != DDP_OK) return rc;
+    if (s->numel == 0) return DDP_OK;
+    if ((rc = check_flat(ctx, flat_local, "ddp_pack", "flat_local")) != DDP_OK) return rc;
+    rc = launch_copy(false, ctx->d_tensors, s->d_copy, s->n_copy, flat_local, false, ctx->nontemporal, stream);
+    return after_launch(ctx, "ddp_pack", rc);
+}
+
+extern "C" int ddp_unpack(ddp_ctx *ctx, int slot, const float *flat, void *stream) {
+    int rc;
+    const SlotTables *s = slot_of(ctx, slot, "ddp_unpack", &rc);
+    if (!s) return rc;
+    if ((rc = check_device(ctx, "ddp_unpack")) != DDP_OK) return rc;
+    if (s->numel == 0) return DDP_OK;
+    if ((rc = check_flat(ctx, flat, "ddp_unpack", "flat")) != DDP_OK) return rc;
+    rc = launch_copy(true, ctx->d_tensors, s->d_copy, s->n_copy, const_cast<float *>(flat), ctx->param_dtype == DDP_BF16,
+                     ctx->nontemporal, stream);
+    return after_launch(ctx, "ddp_unpack", rc);
+}
+
+extern "C" int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_local, const float *const *peers, int N,
+                                   int local_rank, float *flat_out, double *layer_stats, void *stream) {
+    int rc;
+    const SlotTables *s = slot_of(ctx, slot, "ddp_partial_average", &rc);
+    if (!s) return rc;
+    if ((rc = check_device(ctx, "ddp_partial_average")) != DDP_OK) return rc;
+    if (N < 1 || N > DDP_MAX_REPLICAS) return fail(ctx, DDP_EINVAL, "ddp_partial_average: N must be in [1, " + std::to_string((int)DDP_MAX_REPLICAS) + "]");
+    if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, "ddp_partial_average: local_rank out of range");
+    if (N > 1 && !peers) return fail(ctx, DDP_EINVAL, "ddp_partial_average: peers is NULL");
+    if (s->numel == 0) return DDP_OK;
+    if ((rc = check_flat(ctx, flat_local, "ddp_partial_average", "flat_local")) != DDP_OK) return rc;
+    if ((rc = check_flat(ctx, flat_out, "ddp_partial_average", "flat_out")) != DDP_OK) return rc;
+    if (layer_stats && !aligned(layer_stats, 8)) return fail(ctx, DDP_EALIGN, "ddp_partial_average: layer_stats must be 8-byte aligned");
+    const uintptr_t bytes = (uintptr_t)s->numel * 4;
+    auto overlaps = [&](const void *a, const void *b) {
+        uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+        return x < y + bytes && y < x + bytes;
+    };
+    if (flat_out != flat_local && overlaps(flat_out, flat_local))
+        return fail(ctx, DDP_EINVAL, "ddp_partial_average: flat_out partially overlaps flat_local");
+    MeanLaunch a{};
+    int p = 0;
+    for (int k = 0; k < N; ++k) {
+        if (k == local_rank) {
+            a.x[k] = flat_local;
+            continue;
+        }
+        const float *q = peers[p++];
+        if ((rc = check_flat(ctx, q, "ddp_partial_average", "a peer buffer")) != DDP_OK) return rc;
+        if (overlaps(q, flat_out)) return fail(ctx, DDP_EINVAL, "ddp_partial_average: a peer buffer overlaps flat_out");
+        a.x[k] = q;
+    }
+    a.n_replicas = N;
+    a.inv_n = 1.0f / (float)N;
+    a.out = flat_out;
+    a.chunks = s->d_mean;
+    a.n_chunks = s->n_mean;
+    a.partials = layer_stats ? ctx->d_partials : nullptr;
+    a.layer_chunk_ptr = s->d_layer_chunk_ptr;
+    a.n_layers = (int)s->layers.size();
+    a.stats = layer_stats;
+    a.nontemporal = ctx->nontemporal;
+    rc = launch_mean(a, stream);
+    return after_launch(ctx, "ddp_partial_average", rc);
+}
+
+extern "C" int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream) {
+    if (!ctx) return fail(nullptr, DDP_EINVAL, "ddp_local_update: ctx is NULL");
+    if (!ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_local_update: no model registered");
+    if (!opt) return fail(ctx, DDP_EINVAL, "ddp_local_update: opt is NULL");
+    int rc = check_device(ctx, "ddp_local_update");
+    if (rc != DDP_OK) return rc;
+    UpdateScalars s{};
+    if (opt->kind == DDP_OPT_SGDM) {
+        s.lr = opt->lr;
+        s.mu = opt->momentum;
+    } else if (opt->kind == DDP_OPT_ADAMW) {
+        if (!ctx->has_state1) return fail(ctx, DDP_ESTATE, "ddp_local_update: AdamW needs state1_ptr for every tensor");
+        if (opt->step < 1) return fail(ctx, DDP_EINVAL, "ddp_local_update: step is 1-based");
+        if (!(opt->beta1 >= 0.0f && opt->beta1 < 1.0f && opt->beta2 >= 0.0f && opt->beta2 < 1.0f))
+            return fail(ctx, DDP_EINVAL, "ddp_local_update: betas must be in [0, 1)");
+        // bias corrections in fp64, handed to the kernel as fp32 factors
+        const double bc1 = 1.0 - std::pow((double)opt->beta1, (double)opt->step);
+        const double bc2 = 1.0 - std::pow((double)opt->beta2, (double)opt->step);
+        const float inv_bc1 = (float)(1.0 / bc1);
+        s.beta1 = opt->beta1;
+        s.beta2 = opt->beta2;
+        s.omb1 = 1.0f - opt->beta1;
+        s.omb2 = 1.0f - opt->beta2;
+        s.decay = 1.0f - opt->lr * opt->weight_decay;
+        s.step_size = opt->lr * inv_bc1;
+        s.rsqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
+        s.eps = opt->eps;
+    } else {
+        return fail(ctx, DDP_EINVAL, "ddp_local_update: unknown optimizer kind");
+    }
+    rc = launch_update(opt->kind, ctx->grad_dtype, ctx->param_dtype == DDP_BF16, ctx->d_tensors, ctx->d_update, ctx->n_update, s,
+                       ctx->nontemporal, stream);
+    return after_launch(ctx, "ddp_local_update", rc);
+}

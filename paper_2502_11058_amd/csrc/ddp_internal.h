@@ -1,0 +1,118 @@
+// Internal declarations shared by the host side of the library (context, tables) and its kernels.
+#ifndef DDP_INTERNAL_H
+#define DDP_INTERNAL_H
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "dreamddp.h"
+
+namespace ddp {
+
+// Record a failure message (on the context, or thread-local when ctx is NULL) and return the code.
+int fail(const ddp_ctx *ctx, int code, const std::string &msg);
+
+// ---- device tables -------------------------------------------------------------------------------------------
+// Everything a kernel needs to find its work is in small read-only tables in HBM, built once when the model
+// is registered or the schedule installed.  One workgroup handles one "chunk": a run of elements that lies
+// inside one tensor (copy, update) or one layer (mean), so ragged tensor and layer boundaries never fall
+// inside a workgroup's vector loop, and per-layer reductions never mix layers.
+
+struct TensorDesc {   // one registered tensor
+    float *sync;      // fp32 params or master weights
+    uint16_t *model;  // bf16 model copy or nullptr
+    void *grad;       // fp32 or bf16
+    float *state0;    // momentum / first moment
+    float *state1;    // second moment or nullptr
+    int64_t numel;
+};
+
+struct UpdateChunk {  // local_update: elements [begin, begin+count) of tensor `tensor`
+    int64_t begin;
+    int32_t tensor;
+    int32_t count;
+};
+
+struct CopyChunk {  // pack / unpack: tensor elements [t_begin, +count) <-> flat elements [flat_begin, +count)
+    int64_t t_begin;
+    int64_t flat_begin;
+    int32_t tensor;
+    int32_t count;
+};
+
+struct MeanChunk {  // partial_average: flat elements [begin, +count), all inside the slot's layer `layer`
+    int64_t begin;
+    int32_t count;
+    int32_t layer;
+};
+
+struct SlotTables {
+    // host copies (introspection, validation)
+    std::vector<int32_t> layers;       // layer ids in flat order
+    std::vector<int64_t> layer_begin;  // n_layers + 1 flat offsets
+    std::vector<int32_t> tensors;      // tensor ids in flat order
+    std::vector<int64_t> tensor_off;
+    int64_t numel = 0;
+    // device tables
+    CopyChunk *d_copy = nullptr;
+    int64_t n_copy = 0;
+    MeanChunk *d_mean = nullptr;
+    int64_t n_mean = 0;
+    int32_t *d_layer_chunk_ptr = nullptr;  // n_layers + 1: first mean chunk of each layer
+};
+
+// ---- launchers (ddp_kernels.hip) -------------------------------------------------------------------------------
+struct MeanLaunch {
+    const float *x[DDP_MAX_REPLICAS];  // replicas in rank order
+    int n_replicas;
+    float inv_n;
+    float *out;
+    const MeanChunk *chunks;
+    int64_t n_chunks;
+    double *partials;  // [n_chunks][2] or nullptr when no statistics are wanted
+    const int32_t *layer_chunk_ptr;
+    int n_layers;
+    double *stats;  // [n_layers][2]
+    bool nontemporal;
+};
+
+struct UpdateScalars {
+    float lr, mu;                                                // SGD-m
+    float beta1, beta2, omb1, omb2, decay, step_size, rsqrt_bc2, eps;  // AdamW
+};
+
+int launch_copy(bool unpack, const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, float *flat,
+                bool with_model, bool nontemporal, void *stream);
+int launch_mean(const MeanLaunch &a, void *stream);
+int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *tensors, const UpdateChunk *chunks,
+                  int64_t n_chunks, const UpdateScalars &s, bool nontemporal, void *stream);
+
+}  // namespace ddp
+
+struct ddp_ctx {
+    int device = 0;
+    mutable std::string err;
+    // options
+    int64_t update_chunk = 8192, mean_chunk = 8192, copy_chunk = 8192;
+    bool nontemporal = true;
+    // model
+    bool registered = false;
+    int L = 0, T = 0;
+    int param_dtype = DDP_F32, grad_dtype = DDP_F32;
+    bool has_state1 = false;
+    std::vector<int32_t> layer_of;
+    std::vector<int64_t> numel;
+    std::vector<ddp::TensorDesc> tensors;
+    std::vector<int32_t> layer_first_tensor;  // L + 1
+    ddp::TensorDesc *d_tensors = nullptr;
+    ddp::UpdateChunk *d_update = nullptr;
+    int64_t n_update = 0;
+    // schedule
+    int H = 0;
+    std::vector<ddp::SlotTables> slots;
+    double *d_partials = nullptr;  // reduction scratch for per-layer statistics, sized for the largest slot
+    int64_t partials_cap = 0;
+};
+
+#endif

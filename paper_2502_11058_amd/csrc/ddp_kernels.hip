@@ -1,0 +1,558 @@
+// gfx950 kernels of the partial-synchronisation + local-update step (Algorithm 1 / Eq. (5) of the paper).
+//
+// All four kernels are HBM streaming kernels (well under 1 flop per byte): no MFMA, no data reuse.  The design
+// rules are the same everywhere:
+//   - one workgroup (256 threads = 4 wavefronts of 64) per table entry ("chunk"), a run of elements inside one
+//     tensor or one layer, so the ragged boundaries of tensors and layers are handled by the table, not by
+//     per-element searches;
+//   - inside a chunk: a scalar head of < 4 elements up to the next 16-byte boundary of the destination, a body
+//     of 128-bit accesses (lane i of a wavefront touches bytes [16i, 16i+16) of a 1 KiB line, fully coalesced),
+//     and a scalar tail of < 4 elements;
+//   - several independent 128-bit loads are issued before the first use, to keep enough bytes in flight per CU;
+//   - streaming (nontemporal) cache hints, since nothing is read twice;
+//   - floating-point contraction is off: every product and sum below is its own IEEE fp32 operation, and
+//     division and square root are the correctly rounded ones, so results do not depend on instruction selection.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "ddp_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace ddp {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWave = 64;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+
+template <bool NT, class T>
+__device__ __forceinline__ T ld(const T *p) {
+    if constexpr (NT)
+        return __builtin_nontemporal_load(p);
+    else
+        return *p;
+}
+
+template <bool NT, class T>
+__device__ __forceinline__ void st(T *p, T v) {
+    if constexpr (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// fp32 -> bf16, round to nearest, ties to even (add 0x7fff plus the lowest kept bit, then truncate); NaN -> quiet NaN.
+__device__ __forceinline__ unsigned short bf16_rne(float f) {
+    unsigned int u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
+__device__ __forceinline__ float bf16_widen(unsigned short h) { return __uint_as_float(((unsigned int)h) << 16); }
+
+__device__ __forceinline__ u16x4 bf16_rne4(f32x4 v) {
+    u16x4 r;
+    r.x = bf16_rne(v.x);
+    r.y = bf16_rne(v.y);
+    r.z = bf16_rne(v.z);
+    r.w = bf16_rne(v.w);
+    return r;
+}
+
+__device__ __forceinline__ int head_to_16B(const void *p, int n) {  // fp32 elements until p is 16-byte aligned
+    int h = (int)((4u - (unsigned)((reinterpret_cast<uintptr_t>(p) >> 2) & 3u)) & 3u);
+    return h < n ? h : n;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// pack / unpack
+// ---------------------------------------------------------------------------------------------------------------
+
+// Elements [4 - d .. 7 - d] of the 8-element window (a, b): the 4 source elements that start d elements after a.
+__device__ __forceinline__ f32x4 window(f32x4 a, f32x4 b, int d) {
+    switch (d) {
+        case 1: return f32x4{a.y, a.z, a.w, b.x};
+        case 2: return f32x4{a.z, a.w, b.x, b.y};
+        case 3: return f32x4{a.w, b.x, b.y, b.z};
+        default: return a;
+    }
+}
+
+// UNPACK = false: flat[flat_begin + i] = sync[t_begin + i]           (Algorithm 1: operand of the average)
+// UNPACK = true : sync[t_begin + i] = flat[flat_begin + i], and the bf16 model copy = RNE of the same value.
+// Stores are always 16-byte aligned.  When source and destination differ in their offset within a 16-byte
+// granule, each lane loads the two aligned source granules that cover its 4 elements (the second is the next
+// lane's first: it comes from the cache, not from HBM) and picks its window.  Every granule that is loaded
+// holds at least one element of the chunk, so no access leaves the allocation's pages.
+template <bool UNPACK, bool MODEL, bool NT>
+__global__ __launch_bounds__(kThreads) void copy_kernel(const TensorDesc *__restrict__ tensors, const CopyChunk *__restrict__ chunks,
+                                                        float *__restrict__ flat) {
+    const CopyChunk ch = chunks[blockIdx.x];
+    const TensorDesc td = tensors[ch.tensor];
+    float *tptr = td.sync + ch.t_begin;
+    float *fptr = flat + ch.flat_begin;
+    const float *src = UNPACK ? fptr : tptr;
+    float *dst = UNPACK ? tptr : fptr;
+    unsigned short *mdl = MODEL ? td.model + ch.t_begin : reinterpret_cast<unsigned short *>(dst);  // unused without MODEL
+    const int n = ch.count;
+    const int tid = threadIdx.x;
+
+    const int h = head_to_16B(dst, n);
+    if (tid < h) {
+        float v = src[tid];
+        dst[tid] = v;
+        if constexpr (MODEL) mdl[tid] = bf16_rne(v);
+    }
+    const int nv = (n - h) >> 2;
+    const int tail0 = h + 4 * nv;
+    if (tid < n - tail0) {
+        float v = src[tail0 + tid];
+        dst[tail0 + tid] = v;
+        if constexpr (MODEL) mdl[tail0 + tid] = bf16_rne(v);
+    }
+    if (nv == 0) return;
+
+    f32x4 *d4 = reinterpret_cast<f32x4 *>(dst + h);
+    const int delta = (int)((reinterpret_cast<uintptr_t>(src + h) >> 2) & 3u);
+    const bool mdl_vec = MODEL && ((reinterpret_cast<uintptr_t>(mdl + h) & 7u) == 0);
+    u16x4 *m4 = reinterpret_cast<u16x4 *>(mdl + h);
+
+    auto put = [&](int v, f32x4 val) {
+        st<NT>(d4 + v, val);
+        if constexpr (MODEL) {
+            u16x4 b = bf16_rne4(val);
+            if (mdl_vec) {
+                st<NT>(m4 + v, b);
+            } else {
+                unsigned short *m = mdl + h + 4 * v;
+                m[0] = b.x;
+                m[1] = b.y;
+                m[2] = b.z;
+                m[3] = b.w;
+            }
+        }
+    };
+
+    if (delta == 0) {
+        const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src + h);
+        int v = tid;
+        for (; v + 3 * kThreads < nv; v += 4 * kThreads) {
+            f32x4 a0 = ld<NT>(s4 + v);
+            f32x4 a1 = ld<NT>(s4 + v + kThreads);
+            f32x4 a2 = ld<NT>(s4 + v + 2 * kThreads);
+            f32x4 a3 = ld<NT>(s4 + v + 3 * kThreads);
+            put(v, a0);
+            put(v + kThreads, a1);
+            put(v + 2 * kThreads, a2);
+            put(v + 3 * kThreads, a3);
+        }
+        for (; v < nv; v += kThreads) put(v, ld<NT>(s4 + v));
+    } else {
+        // aligned granule that holds the first source element of the body
+        const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src + h - delta);
+        // the last vector's second granule would start past the chunk's last element only if it held none of
+        // the 4 wanted elements, which cannot happen for delta != 0
+        int v = tid;
+        for (; v + kThreads < nv; v += 2 * kThreads) {
+            f32x4 a0 = s4[v], b0 = s4[v + 1];
+            f32x4 a1 = s4[v + kThreads], b1 = s4[v + kThreads + 1];
+            put(v, window(a0, b0, delta));
+            put(v + kThreads, window(a1, b1, delta));
+        }
+        for (; v < nv; v += kThreads) put(v, window(s4[v], s4[v + 1], delta));
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// partial average
+// ---------------------------------------------------------------------------------------------------------------
+
+struct MeanArgs {
+    const float *x[DDP_MAX_REPLICAS];
+    float *out;
+    const MeanChunk *chunks;
+    double *partials;
+    float inv_n;
+    int n;
+};
+
+// Sum of a double over the workgroup in a fixed order: butterfly-free shuffle-down tree inside each wavefront,
+// then the four wavefront sums added in wavefront order by thread 0.  Result valid in thread 0.
+__device__ __forceinline__ double block_sum(double v, double *lds) {
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (lane == 0) lds[wave] = v;
+    __syncthreads();
+    double r = 0.0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 0; w < kThreads / kWave; ++w) r += lds[w];
+    }
+    __syncthreads();
+    return r;
+}
+
+// Eq. (5), second case.  NREP > 0: replica count known at compile time (pointer loads and the sum fully
+// unrolled); NREP == 0: run-time count.  The sum runs left to right over replicas in rank order, in fp32, then
+// one multiply by 1/N.  STATS adds, per chunk, sum_k sum_i (out_i - x_k,i)^2 and sum_i out_i^2 in fp64.
+template <int NREP, bool STATS, bool NT>
+__global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
+    __shared__ double lds[2][kThreads / kWave];
+    const MeanChunk ch = a.chunks[blockIdx.x];
+    const int n = ch.count;
+    const int tid = threadIdx.x;
+    const int nrep = NREP > 0 ? NREP : a.n;
+    const float inv_n = a.inv_n;
+    const int64_t base = ch.begin;
+    double gsum = 0.0, msum = 0.0;
+
+    auto one = [&](int64_t i) {
+        float acc = a.x[0][i];
+        for (int k = 1; k < nrep; ++k) acc = acc + a.x[k][i];
+        const float m = acc * inv_n;
+        if constexpr (STATS) {
+            for (int k = 0; k < nrep; ++k) {
+                const float d = m - a.x[k][i];
+                gsum += (double)d * (double)d;
+            }
+            msum += (double)m * (double)m;
+        }
+        a.out[i] = m;
+    };
+
+    // all buffers are 16-byte aligned at element 0, so the flat index decides the alignment
+    int h = (int)((4 - (base & 3)) & 3);
+    if (h > n) h = n;
+    if (tid < h) one(base + tid);
+    const int nv = (n - h) >> 2;
+    const int tail0 = h + 4 * nv;
+    if (tid < n - tail0) one(base + tail0 + tid);
+
+    const int64_t vbase = (base + h) >> 2;  // index in 16-byte units
+    f32x4 *o4 = reinterpret_cast<f32x4 *>(a.out) + vbase;
+
+    auto stats4 = [&](f32x4 m, f32x4 x) {
+        const f32x4 d = m - x;
+        gsum += (double)d.x * (double)d.x;
+        gsum += (double)d.y * (double)d.y;
+        gsum += (double)d.z * (double)d.z;
+        gsum += (double)d.w * (double)d.w;
+    };
+    auto msq4 = [&](f32x4 m) {
+        msum += (double)m.x * (double)m.x;
+        msum += (double)m.y * (double)m.y;
+        msum += (double)m.z * (double)m.z;
+        msum += (double)m.w * (double)m.w;
+    };
+
+    if constexpr (NREP > 0) {
+        constexpr int B = NREP <= 4 ? 4 : (NREP <= 8 ? 2 : 1);  // vectors per thread in flight: B * NREP loads
+        int v = tid;
+        for (; v + (B - 1) * kThreads < nv; v += B * kThreads) {
+            f32x4 x[B][NREP];
+#pragma unroll
+            for (int b = 0; b < B; ++b)
+#pragma unroll
+                for (int k = 0; k < NREP; ++k) x[b][k] = ld<NT>(reinterpret_cast<const f32x4 *>(a.x[k]) + vbase + v + b * kThreads);
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                f32x4 acc = x[b][0];
+#pragma unroll
+                for (int k = 1; k < NREP; ++k) acc = acc + x[b][k];
+                const f32x4 m = acc * inv_n;
+                if constexpr (STATS) {
+#pragma unroll
+                    for (int k = 0; k < NREP; ++k) stats4(m, x[b][k]);
+                    msq4(m);
+                }
+                st<NT>(o4 + v + b * kThreads, m);
+            }
+        }
+        for (; v < nv; v += kThreads) {
+            f32x4 x[NREP];
+#pragma unroll
+            for (int k = 0; k < NREP; ++k) x[k] = ld<NT>(reinterpret_cast<const f32x4 *>(a.x[k]) + vbase + v);
+            f32x4 acc = x[0];
+#pragma unroll
+            for (int k = 1; k < NREP; ++k) acc = acc + x[k];
+            const f32x4 m = acc * inv_n;
+            if constexpr (STATS) {
+#pragma unroll
+                for (int k = 0; k < NREP; ++k) stats4(m, x[k]);
+                msq4(m);
+            }
+            st<NT>(o4 + v, m);
+        }
+    } else {
+        for (int v = tid; v < nv; v += kThreads) {
+            f32x4 acc = ld<NT>(reinterpret_cast<const f32x4 *>(a.x[0]) + vbase + v);
+            for (int k = 1; k < nrep; ++k) acc = acc + ld<NT>(reinterpret_cast<const f32x4 *>(a.x[k]) + vbase + v);
+            const f32x4 m = acc * inv_n;
+            if constexpr (STATS) {
+                for (int k = 0; k < nrep; ++k) stats4(m, reinterpret_cast<const f32x4 *>(a.x[k])[vbase + v]);
+                msq4(m);
+            }
+            st<NT>(o4 + v, m);
+        }
+    }
+
+    if constexpr (STATS) {
+        const double g = block_sum(gsum, lds[0]);
+        const double m = block_sum(msum, lds[1]);
+        if (tid == 0) {
+            a.partials[2 * (int64_t)blockIdx.x] = g;
+            a.partials[2 * (int64_t)blockIdx.x + 1] = m;
+        }
+    }
+}
+
+// Per layer: add the chunk partials of that layer in a fixed order (thread-strided, then the workgroup tree) and
+// scale the divergence by 1/N (Sec. 3.4: Gamma = 1/K sum_k ||wbar - w^k||^2, here per layer).
+__global__ __launch_bounds__(kThreads) void stats_finalize_kernel(const double *__restrict__ partials,
+                                                                  const int32_t *__restrict__ layer_chunk_ptr, int n_replicas,
+                                                                  double *__restrict__ stats) {
+    __shared__ double lds[2][kThreads / kWave];
+    const int l = blockIdx.x;
+    const int c0 = layer_chunk_ptr[l], c1 = layer_chunk_ptr[l + 1];
+    double g = 0.0, m = 0.0;
+    for (int c = c0 + (int)threadIdx.x; c < c1; c += kThreads) {
+        g += partials[2 * (int64_t)c];
+        m += partials[2 * (int64_t)c + 1];
+    }
+    g = block_sum(g, lds[0]);
+    m = block_sum(m, lds[1]);
+    if (threadIdx.x == 0) {
+        stats[2 * l] = g / (double)n_replicas;
+        stats[2 * l + 1] = m;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// local update
+// ---------------------------------------------------------------------------------------------------------------
+
+// buf = mu*buf + g;  p = p - lr*buf
+__device__ __forceinline__ void sgdm_one(float g, float &p, float &buf, const UpdateScalars &s) {
+    float b = s.mu * buf;
+    b = b + g;
+    buf = b;
+    const float u = s.lr * b;
+    p = p - u;
+}
+
+// m = beta1*m + (1-beta1)*g;  v = beta2*v + ((1-beta2)*g)*g;  p = p*decay;  p = p - step_size*(m / (sqrt(v)*rsqrt_bc2 + eps))
+__device__ __forceinline__ void adamw_one(float g, float &p, float &m, float &v, const UpdateScalars &s) {
+    const float a = s.beta1 * m;
+    const float b = s.omb1 * g;
+    const float mi = a + b;
+    const float c = s.beta2 * v;
+    const float d = s.omb2 * g;
+    const float e = d * g;
+    const float vi = c + e;
+    float pi = p * s.decay;
+    const float r = __fsqrt_rn(vi);
+    float den = r * s.rsqrt_bc2;
+    den = den + s.eps;
+    const float q = __fdiv_rn(mi, den);
+    const float u = s.step_size * q;
+    pi = pi - u;
+    m = mi;
+    v = vi;
+    p = pi;
+}
+
+template <bool BF16>
+struct GradVec;
+template <>
+struct GradVec<false> {
+    typedef float elem;
+    typedef f32x4 vec;
+    static __device__ __forceinline__ f32x4 widen(f32x4 g) { return g; }
+    static __device__ __forceinline__ float widen1(float g) { return g; }
+};
+template <>
+struct GradVec<true> {
+    typedef unsigned short elem;
+    typedef u16x4 vec;
+    static __device__ __forceinline__ f32x4 widen(u16x4 g) {
+        return f32x4{bf16_widen(g.x), bf16_widen(g.y), bf16_widen(g.z), bf16_widen(g.w)};
+    }
+    static __device__ __forceinline__ float widen1(unsigned short g) { return bf16_widen(g); }
+};
+
+// Eq. (5), first case, fused: one pass reads gradient, parameter and optimizer state and writes parameter,
+// state and (if present) the bf16 model copy.  ADAM selects AdamW, else SGD with momentum.
+template <bool ADAM, bool GBF16, bool MODEL, bool NT>
+__global__ __launch_bounds__(kThreads) void update_kernel(const TensorDesc *__restrict__ tensors, const UpdateChunk *__restrict__ chunks,
+                                                          const UpdateScalars s) {
+    typedef GradVec<GBF16> G;
+    typedef typename G::elem gelem;
+    typedef typename G::vec gvec;
+    const UpdateChunk ch = chunks[blockIdx.x];
+    const TensorDesc td = tensors[ch.tensor];
+    float *p = td.sync + ch.begin;
+    float *s0 = td.state0 + ch.begin;
+    float *s1 = ADAM ? td.state1 + ch.begin : s0;  // unused without ADAM
+    const gelem *g = reinterpret_cast<const gelem *>(td.grad) + ch.begin;
+    unsigned short *mdl = MODEL ? td.model + ch.begin : reinterpret_cast<unsigned short *>(p);  // unused without MODEL
+    const int n = ch.count;
+    const int tid = threadIdx.x;
+
+    auto one = [&](int i) {
+        float pi = p[i], a = s0[i];
+        const float gi = G::widen1(g[i]);
+        if constexpr (ADAM) {
+            float b = s1[i];
+            adamw_one(gi, pi, a, b, s);
+            s1[i] = b;
+        } else {
+            sgdm_one(gi, pi, a, s);
+        }
+        p[i] = pi;
+        s0[i] = a;
+        if constexpr (MODEL) mdl[i] = bf16_rne(pi);
+    };
+
+    // 128-bit path needs every stream to reach its vector alignment after the same head
+    const int h = head_to_16B(p, n);
+    bool vec_ok = (reinterpret_cast<uintptr_t>(s0 + h) & 15u) == 0;
+    if constexpr (ADAM) vec_ok = vec_ok && (reinterpret_cast<uintptr_t>(s1 + h) & 15u) == 0;
+    vec_ok = vec_ok && (reinterpret_cast<uintptr_t>(g + h) & (sizeof(gvec) - 1)) == 0;
+    if constexpr (MODEL) vec_ok = vec_ok && (reinterpret_cast<uintptr_t>(mdl + h) & 7u) == 0;
+    if (!vec_ok) {
+        for (int i = tid; i < n; i += kThreads) one(i);
+        return;
+    }
+
+    if (tid < h) one(tid);
+    const int nv = (n - h) >> 2;
+    const int tail0 = h + 4 * nv;
+    if (tid < n - tail0) one(tail0 + tid);
+
+    f32x4 *p4 = reinterpret_cast<f32x4 *>(p + h);
+    f32x4 *a4 = reinterpret_cast<f32x4 *>(s0 + h);
+    f32x4 *b4 = reinterpret_cast<f32x4 *>(s1 + h);
+    const gvec *g4 = reinterpret_cast<const gvec *>(g + h);
+    u16x4 *m4 = reinterpret_cast<u16x4 *>(mdl + h);
+
+    auto compute_store = [&](int v, gvec gv, f32x4 pv, f32x4 av, f32x4 bv) {
+        const f32x4 gw = G::widen(gv);
+        float G4[4] = {gw.x, gw.y, gw.z, gw.w};
+        float P4[4] = {pv.x, pv.y, pv.z, pv.w};
+        float A4[4] = {av.x, av.y, av.z, av.w};
+        float B4[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (ADAM)
+                adamw_one(G4[j], P4[j], A4[j], B4[j], s);
+            else
+                sgdm_one(G4[j], P4[j], A4[j], s);
+        }
+        const f32x4 pn{P4[0], P4[1], P4[2], P4[3]};
+        st<NT>(p4 + v, pn);
+        st<NT>(a4 + v, f32x4{A4[0], A4[1], A4[2], A4[3]});
+        if constexpr (ADAM) st<NT>(b4 + v, f32x4{B4[0], B4[1], B4[2], B4[3]});
+        if constexpr (MODEL) st<NT>(m4 + v, bf16_rne4(pn));
+    };
+
+    int v = tid;
+    for (; v + kThreads < nv; v += 2 * kThreads) {
+        const int w = v + kThreads;
+        gvec g0 = ld<NT>(g4 + v), g1 = ld<NT>(g4 + w);
+        f32x4 p0 = ld<NT>(p4 + v), p1 = ld<NT>(p4 + w);
+        f32x4 a0 = ld<NT>(a4 + v), a1 = ld<NT>(a4 + w);
+        f32x4 b0{}, b1{};
+        if constexpr (ADAM) {
+            b0 = ld<NT>(b4 + v);
+            b1 = ld<NT>(b4 + w);
+        }
+        compute_store(v, g0, p0, a0, b0);
+        compute_store(w, g1, p1, a1, b1);
+    }
+    for (; v < nv; v += kThreads) {
+        gvec g0 = ld<NT>(g4 + v);
+        f32x4 p0 = ld<NT>(p4 + v);
+        f32x4 a0 = ld<NT>(a4 + v);
+        f32x4 b0{};
+        if constexpr (ADAM) b0 = ld<NT>(b4 + v);
+        compute_store(v, g0, p0, a0, b0);
+    }
+}
+
+template <class K, class... Args>
+int launch(K kernel, int64_t grid, void *stream, Args... args) {
+    if (grid <= 0) return 0;
+    if (grid > 0x7fffffff) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, args...);
+    return (int)hipGetLastError();
+}
+
+template <int NREP>
+int launch_mean_n(const MeanArgs &ma, const MeanLaunch &a, void *stream) {
+    if (a.partials) return a.nontemporal ? launch(mean_kernel<NREP, true, true>, a.n_chunks, stream, ma) : launch(mean_kernel<NREP, true, false>, a.n_chunks, stream, ma);
+    return a.nontemporal ? launch(mean_kernel<NREP, false, true>, a.n_chunks, stream, ma) : launch(mean_kernel<NREP, false, false>, a.n_chunks, stream, ma);
+}
+
+}  // namespace
+
+int launch_copy(bool unpack, const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, float *flat, bool with_model,
+                bool nontemporal, void *stream) {
+    if (!unpack) return nontemporal ? launch(copy_kernel<false, false, true>, n_chunks, stream, tensors, chunks, flat)
+                                    : launch(copy_kernel<false, false, false>, n_chunks, stream, tensors, chunks, flat);
+    if (with_model) return nontemporal ? launch(copy_kernel<true, true, true>, n_chunks, stream, tensors, chunks, flat)
+                                       : launch(copy_kernel<true, true, false>, n_chunks, stream, tensors, chunks, flat);
+    return nontemporal ? launch(copy_kernel<true, false, true>, n_chunks, stream, tensors, chunks, flat)
+                       : launch(copy_kernel<true, false, false>, n_chunks, stream, tensors, chunks, flat);
+}
+
+int launch_mean(const MeanLaunch &a, void *stream) {
+    MeanArgs ma{};
+    for (int k = 0; k < a.n_replicas; ++k) ma.x[k] = a.x[k];
+    ma.out = a.out;
+    ma.chunks = a.chunks;
+    ma.partials = a.partials;
+    ma.inv_n = a.inv_n;
+    ma.n = a.n_replicas;
+    int rc;
+    switch (a.n_replicas) {
+        case 1: rc = launch_mean_n<1>(ma, a, stream); break;
+        case 2: rc = launch_mean_n<2>(ma, a, stream); break;
+        case 3: rc = launch_mean_n<3>(ma, a, stream); break;
+        case 4: rc = launch_mean_n<4>(ma, a, stream); break;
+        case 5: rc = launch_mean_n<5>(ma, a, stream); break;
+        case 6: rc = launch_mean_n<6>(ma, a, stream); break;
+        case 7: rc = launch_mean_n<7>(ma, a, stream); break;
+        case 8: rc = launch_mean_n<8>(ma, a, stream); break;
+        case 16: rc = launch_mean_n<16>(ma, a, stream); break;
+        default: rc = launch_mean_n<0>(ma, a, stream); break;
+    }
+    if (rc != 0 || !a.partials) return rc;
+    return launch(stats_finalize_kernel, a.n_layers, stream, (const double *)a.partials, a.layer_chunk_ptr, a.n_replicas, a.stats);
+}
+
+int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *tensors, const UpdateChunk *chunks, int64_t n_chunks,
+                  const UpdateScalars &s, bool nontemporal, void *stream) {
+    const bool adam = kind == DDP_OPT_ADAMW, gb = grad_dtype == DDP_BF16;
+#define DDP_UPD(A, G, M)                                                                               \
+    if (adam == A && gb == G && with_model == M)                                                       \
+        return nontemporal ? launch(update_kernel<A, G, M, true>, n_chunks, stream, tensors, chunks, s) \
+                           : launch(update_kernel<A, G, M, false>, n_chunks, stream, tensors, chunks, s);
+    DDP_UPD(false, false, false)
+    DDP_UPD(false, false, true)
+    DDP_UPD(false, true, false)
+    DDP_UPD(false, true, true)
+    DDP_UPD(true, false, false)
+    DDP_UPD(true, false, true)
+    DDP_UPD(true, true, false)
+    DDP_UPD(true, true, true)
+#undef DDP_UPD
+    return (int)hipErrorInvalidValue;
+}
+
+}  // namespace ddp

@@ -1,0 +1,131 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports what the header declares, and its
+CPU scheduler agrees with the oracle's exhaustive search and with the oracle's Algorithm 2, bit for bit."""
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2502_11058_amd import binding as B
+from paper_2502_11058_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if fn.endswith(".h"):
+            text = open(os.path.join(inc, fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names += re.findall(r"\b(ddp_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = B.lib()
+    declared = _declared_functions()
+    assert len(declared) >= 15
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(B.EXPORTS) == declared
+
+
+def test_create_without_gpu_fails_cleanly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(B.DdpError) as e:
+        B.Context(0)
+    assert e.value.code in (1, 5)
+
+
+def _sets(policy, L, H, bp=None, comm=None):
+    slot, sp, sl, cost = B.ddp_schedule(policy, L, H, None, bp, comm)
+    return B.sets_from_csr(sp, sl), slot, cost
+
+
+def test_opt_equals_brute_force_small(oracle):
+    rng = np.random.default_rng(10)
+    for _ in range(1500):
+        L, H = int(rng.integers(1, 7)), int(rng.integers(1, 4))
+        bp = rng.integers(0, 12, L)
+        comm = rng.integers(0, 25, L)
+        sizes, cost, _ = oracle.sched_brute(bp, comm, H)
+        sets, slot, c = _sets("opt", L, H, bp, comm)
+        assert sets == oracle.sets_from_sizes(L, sizes) and c == cost
+        for s, S in enumerate(sets):
+            assert all(slot[l] == s for l in S)
+
+
+def test_opt_equals_brute_force_larger(oracle):
+    rng = np.random.default_rng(11)
+    for _ in range(60):
+        L, H = int(rng.integers(7, 13)), int(rng.integers(2, 6))
+        bp = rng.integers(1, 1000, L)
+        comm = rng.integers(1, 4000, L)
+        sizes, cost, n = oracle.sched_brute(bp, comm, H)
+        assert n == math.comb(L + H - 1, H - 1)
+        sets, _, c = _sets("opt", L, H, bp, comm)
+        assert sets == oracle.sets_from_sizes(L, sizes) and c == cost
+
+
+def test_alg2_equals_oracle_alg2(oracle):
+    rng = np.random.default_rng(12)
+    for _ in range(1500):
+        L, H = int(rng.integers(1, 14)), int(rng.integers(1, 7))
+        bp = rng.integers(0, 30, L)
+        comm = rng.integers(0, 60, L)
+        sizes, cost, omega = oracle.sched_alg2(bp, comm, H)
+        sets, _, c = _sets("alg2", L, H, bp, comm)
+        assert sets == oracle.sets_from_sizes(L, sizes) and c == cost
+        assert B.ddp_schedule_alg2_solutions(bp, comm, H) == len(omega)
+        assert c >= _sets("opt", L, H, bp, comm)[2]
+
+
+def test_counter_example_of_optimal_hiding():
+    bp, comm = [1, 1, 8, 1, 2], [2, 5, 2, 1, 9]
+    assert _sets("alg2", 5, 2, bp, comm)[0::2] == ([[4, 3, 2], [1, 0]], 33)
+    assert _sets("opt", 5, 2, bp, comm)[0::2] == ([[4], [3, 2, 1, 0]], 26)
+
+
+@pytest.mark.parametrize("name", ["gpt2_small", "tinyllama_1b", "llama2_7b", "llama3_8b", "small_llama"])
+def test_workload_schedules_match_oracle(oracle, name):
+    w = W.get(name)
+    fp, bp, comm = W.synthetic_times(w)
+    L, H = w.n_layers, w.period
+    for policy in ("enp", "round_robin", "full", "every", "alg2") + (("opt",) if math.comb(L + H - 1, H - 1) < 3e7 else ()):
+        sets, slot, cost = _sets(policy, L, H, bp, comm)
+        assert sets == oracle.schedule(policy, L, H, bp, comm), policy
+        if policy in ("enp", "full", "opt", "alg2"):
+            assert cost == oracle.sched_cost(bp, comm, [len(S) for S in sets])
+
+
+def test_schedule_cost_entry_point(oracle):
+    rng = np.random.default_rng(13)
+    for _ in range(200):
+        L, H = int(rng.integers(1, 9)), int(rng.integers(1, 5))
+        bp = rng.integers(0, 30, L)
+        comm = rng.integers(0, 60, L)
+        cuts = sorted(rng.integers(0, L + 1, H - 1).tolist())
+        edges = [0] + cuts + [L]
+        sizes = [edges[i + 1] - edges[i] for i in range(H)]
+        sets = oracle.sets_from_sizes(L, sizes)
+        sp = np.cumsum([0] + sizes)
+        sl = [l for S in sets for l in S]
+        assert B.ddp_schedule_cost(bp, comm, sp, sl or [0]) == oracle.sched_cost(bp, comm, sizes)
+    with pytest.raises(B.DdpError) as e:
+        B.ddp_schedule_cost([1, 1], [1, 1], [0, 1, 2], [0, 1])       # not in BP order
+    assert e.value.code == 6
+
+
+def test_schedule_argument_errors():
+    for args in [("opt", 0, 2, None, [1], [1]), ("opt", 2, 0, None, [1, 1], [1, 1]), ("opt", 2, 2, None, None, None),
+                 ("opt", 2, 2, None, [1, -1], [1, 1]), ("alg2", 2, 2, None, [2 ** 62, 2 ** 62], [1, 1])]:
+        with pytest.raises(B.DdpError) as e:
+            B.ddp_schedule(*args)
+        assert e.value.code == 1 and len(str(e.value)) > 10
+    with pytest.raises(B.DdpError):
+        B.ddp_schedule(17, 2, 2, None, [1, 1], [1, 1])
