@@ -356,10 +356,10 @@ __device__ __forceinline__ void adamw_one(float g, float &p, float &m, float &v,
     const float e = d * g;
     const float vi = c + e;
     float pi = p * s.decay;
-    const float r = __fsqrt_rn(vi);
+    const float r = __builtin_sqrtf(vi);  // correctly rounded (hipcc default -fhip-fp32-correctly-rounded-divide-sqrt)
     float den = r * s.rsqrt_bc2;
     den = den + s.eps;
-    const float q = __fdiv_rn(mi, den);
+    const float q = mi / den;  // IEEE division, correctly rounded
     const float u = s.step_size * q;
     pi = pi - u;
     m = mi;

@@ -109,29 +109,44 @@ def run_trajectory(oracle, w, policy=None, iters=None, arena_offset=0, options=N
         assert lid.tolist() == list(S)
         ranges = wk.layer_ranges(S, off, order_t)
         assert lbeg.tolist() == [b for b, _ in ranges] + [total]
-        # pack
-        flat_ref = wk.pack_slot(S)[0]
+        # pack: against an independent gather of the same device tensors (torch.cat in the oracle's order)
+        dev_flat = torch.cat([rep.sync[t] for t in order_t]) if total else rep.flat[:0]
+        local_host = _np(dev_flat)
         rep.flat.fill_(float("nan"))
         rep.ctx.ddp_pack(slot, rep.flat)
-        assert np.array_equal(_bits(_np(rep.flat[:total])), _bits(flat_ref)), f"pack r={r}"
-        # peers: oracle-side flat + seeded drift, same bytes to both sides
-        rep.fill_peers_from(torch.from_numpy(flat_ref).to(rep.dev) if total else rep.flat, r, total)
+        assert np.array_equal(_bits(_np(rep.flat[:total])), _bits(local_host)), f"pack r={r}"
+        assert np.array_equal(_bits(oracle.pack([_np(rep.sync[t]) for t in order_t], [off[t] for t in order_t], total)),
+                              _bits(local_host))
+        # peers: gathered local values + seeded drift; the same bytes go to both sides
+        rep.fill_peers_from(dev_flat, r, total)
         peers_host = [_np(p[:total]) for p in rep.peers]
-        # average + statistics
+        # average + statistics: bit-exact given the same inputs
         out.fill_(float("nan"))
         rep.stats.fill_(-1.0)
         rep.ctx.ddp_partial_average(slot, rep.flat, rep.peers, N, rank, out, rep.stats)
-        reps = peers_host[:rank] + [flat_ref] + peers_host[rank:]
-        mean_ref = oracle.mean(reps) if total else flat_ref
+        reps = peers_host[:rank] + [local_host] + peers_host[rank:]
+        mean_ref = oracle.mean(reps) if total else local_host
         assert np.array_equal(_bits(_np(out[:total])), _bits(mean_ref)), f"mean r={r}"
         st = _np(rep.stats)
         for i, (b, e) in enumerate(ranges):
             g, m = oracle.layer_stats(reps, mean_ref, b, e)
             assert st[2 * i] == pytest.approx(g, rel=1e-10, abs=1e-300), f"gamma r={r} layer {S[i]}"
             assert st[2 * i + 1] == pytest.approx(m, rel=1e-10), f"msq r={r} layer {S[i]}"
-        # unpack
+        # in-place variant (flat_out == flat_local) gives the same bits
+        rep.ctx.ddp_partial_average(slot, rep.flat, rep.peers, N, rank, rep.flat, None)
+        assert torch.equal(rep.flat[:total].view(torch.int32), out[:total].view(torch.int32)), f"in-place mean r={r}"
+        # unpack: the scheduled tensors now hold the average, the model copy its bf16 rounding, nothing else moved
+        before = rep.a_sync.clone()
         rep.ctx.ddp_unpack(slot, out)
-        wk.unpack_slot(mean_ref, off, order_t)
+        expect = before
+        for t in order_t:
+            expect[int(rep.offsets[t]): int(rep.offsets[t]) + rep.numel[t]] = out[int(off[t]): int(off[t]) + rep.numel[t]]
+        assert torch.equal(rep.a_sync.view(torch.int32), expect.view(torch.int32)), f"unpack r={r}"
+        if rep.bf16:
+            for t in order_t:
+                assert np.array_equal(_np(rep.model[t]), oracle.bf16_rne(mean_ref[int(off[t]): int(off[t]) + rep.numel[t]])), f"model copy r={r} t={t}"
+        # the carried oracle worker takes the same step from its own state
+        wk.sync(S, peers_host, rank)
         if order == 0:
             update_both(r)
         if (r + 1) % check_every == 0 or r == iters - 1:
