@@ -46,6 +46,9 @@ def lib():
     """Load the library built in-tree (python -m paper_2502_11058_amd.build, or __graft_entry__.build())."""
     global _lib
     if _lib is None:
+        # torch first: the library must share torch's HIP runtime (streams and device pointers come from torch),
+        # and whichever copy of libamdhip64 is loaded first serves every later library of the process
+        import torch  # noqa: F401
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is missing: build it first (python __graft_entry__.py)")
         l = C.CDLL(LIB_PATH)
