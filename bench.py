@@ -112,10 +112,8 @@ def main() -> int:
         return 3
     w = W.get(args.workload)
     options = {k: int(v) for k, v in (o.split("=") for o in args.option)}
-    rep = DeviceReplica(w, 0, options=options)
+    rep = DeviceReplica(w, 0, options=options, policy=args.policy)
     rep.init_params()
-    rep.set_schedule(args.policy)
-    rep.alloc_peers()
     rep.fill_grads(0)
     # peers: slot 0's packed local values + seeded drift; later slots reuse the staged bytes (same distribution)
     rep.ctx.ddp_pack(0, rep.flat)

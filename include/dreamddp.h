@@ -96,6 +96,8 @@ int ddp_destroy(ddp_ctx *ctx);
 /* Tuning knobs, to be set before ddp_register_model / ddp_set_schedule (they shape the tables built there):
  *   "update_chunk", "mean_chunk", "copy_chunk"  elements per workgroup (multiple of 1024, 1024..1048576)
  *   "nontemporal"                               0/1: streaming cache hints on loads and stores
+ *   "dispatch_ways"                             1..4096: launch order of the workgroups; w > 1 cuts every chunk table
+ *                                               into w contiguous segments and visits them round-robin
  * Unknown names or bad values: DDP_EINVAL. */
 int ddp_set_option(ddp_ctx *ctx, const char *name, int64_t value);
 

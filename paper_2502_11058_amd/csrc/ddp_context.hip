@@ -84,6 +84,26 @@ static int after_launch(const ddp_ctx *c, const char *who, int hip_rc) {
     return fail(c, DDP_EHIP, std::string(who) + ": kernel launch failed: " + hipGetErrorString((hipError_t)hip_rc));
 }
 
+// Dispatch order of a chunk table.  Workgroups are handed to the 8 XCDs round-robin in launch order, and the
+// resident workgroups of a launch form a moving window over the table.  With `ways` > 1 the table is cut into
+// `ways` contiguous segments and launch position j takes entry j / ways of segment j % ways: the window then
+// covers `ways` far-apart regions of every stream at once instead of one contiguous region, and with ways a
+// multiple of 8 each XCD walks its own segments front to back.
+template <class T>
+static void interleave_segments(std::vector<T> &v, int ways) {
+    const size_t n = v.size();
+    if (ways <= 1 || n < (size_t)ways * 2) return;
+    const size_t seg = (n + (size_t)ways - 1) / (size_t)ways;
+    std::vector<T> out;
+    out.reserve(n);
+    for (size_t i = 0; i < seg; ++i)
+        for (size_t s = 0; s < (size_t)ways; ++s) {
+            const size_t idx = s * seg + i;
+            if (idx < n) out.push_back(v[idx]);
+        }
+    v.swap(out);
+}
+
 static bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 }  // namespace ddp
@@ -123,6 +143,12 @@ extern "C" int ddp_set_option(ddp_ctx *ctx, const char *name, int64_t value) {
         if (!chunk_ok(value)) return fail(ctx, DDP_EINVAL, "ddp_set_option: chunk must be a multiple of 1024 in [1024, 1048576]");
         if (ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_set_option: chunk sizes must be set before ddp_register_model");
         (k == "update_chunk" ? ctx->update_chunk : k == "mean_chunk" ? ctx->mean_chunk : ctx->copy_chunk) = value;
+        return DDP_OK;
+    }
+    if (k == "dispatch_ways") {
+        if (value < 1 || value > 4096) return fail(ctx, DDP_EINVAL, "ddp_set_option: dispatch_ways must be in [1, 4096]");
+        if (ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_set_option: dispatch_ways must be set before ddp_register_model");
+        ctx->dispatch_ways = (int)value;
         return DDP_OK;
     }
     if (k == "nontemporal") {
@@ -192,6 +218,7 @@ extern "C" int ddp_register_model(ddp_ctx *ctx, int L, int T, const int32_t *lay
             int64_t n = std::min<int64_t>(ctx->update_chunk, numel[t] - b);
             uc.push_back({b, t, (int32_t)n});
         }
+    interleave_segments(uc, ctx->dispatch_ways);
     rc = upload(ctx, ts, &ctx->d_tensors);
     if (rc == DDP_OK) rc = upload(ctx, uc, &ctx->d_update);
     if (rc != DDP_OK) {
@@ -250,7 +277,7 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
             int64_t b = layer_start;
             while (b < off) {
                 int64_t e = std::min<int64_t>(off, (b / 4) * 4 + ctx->mean_chunk);
-                mc.push_back({b, (int32_t)(e - b), (int32_t)(j - set_ptr[s])});
+                mc.push_back({b, (int32_t)(e - b), (int32_t)mc.size()});
                 b = e;
             }
         }
@@ -260,6 +287,8 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
         st.n_copy = (int64_t)cc.size();
         st.n_mean = (int64_t)mc.size();
         max_mean_chunks = std::max(max_mean_chunks, st.n_mean);
+        interleave_segments(cc, ctx->dispatch_ways);
+        interleave_segments(mc, ctx->dispatch_ways);
         rc = upload(ctx, cc, &st.d_copy);
         if (rc == DDP_OK) rc = upload(ctx, mc, &st.d_mean);
         if (rc == DDP_OK) rc = upload(ctx, lcp, &st.d_layer_chunk_ptr);

@@ -41,10 +41,10 @@ struct CopyChunk {  // pack / unpack: tensor elements [t_begin, +count) <-> flat
     int32_t count;
 };
 
-struct MeanChunk {  // partial_average: flat elements [begin, +count), all inside the slot's layer `layer`
+struct MeanChunk {  // partial_average: flat elements [begin, +count), all inside one layer of the slot
     int64_t begin;
     int32_t count;
-    int32_t layer;
+    int32_t partial;  // where this chunk's partial sums go: its index in flat order, whatever the dispatch order
 };
 
 struct SlotTables {
@@ -96,6 +96,7 @@ struct ddp_ctx {
     // options
     int64_t update_chunk = 8192, mean_chunk = 8192, copy_chunk = 8192;
     bool nontemporal = true;
+    int dispatch_ways = 1;
     // model
     bool registered = false;
     int L = 0, T = 0;

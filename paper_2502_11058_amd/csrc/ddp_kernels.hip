@@ -306,8 +306,8 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
         const double g = block_sum(gsum, lds[0]);
         const double m = block_sum(msum, lds[1]);
         if (tid == 0) {
-            a.partials[2 * (int64_t)blockIdx.x] = g;
-            a.partials[2 * (int64_t)blockIdx.x + 1] = m;
+            a.partials[2 * (int64_t)ch.partial] = g;
+            a.partials[2 * (int64_t)ch.partial + 1] = m;
         }
     }
 }

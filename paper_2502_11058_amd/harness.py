@@ -2,9 +2,10 @@
 drives the four calls of an iteration.  Allocation, seeding and call order only; all arithmetic of the method
 happens inside the library.
 
-HBM layout: one flat arena per stream (fp32 master/params, bf16 model copy, gradient, optimizer state 0 and 1),
-every tensor a view at its dense offset in registration order, so a kernel sees a handful of long contiguous
-streams rather than hundreds of separate allocations.
+HBM layout: ONE slab per worker, cut into 2 MiB-aligned regions: one flat arena per stream (fp32 master/params,
+optimizer state 0 and 1, gradient, bf16 model copy), then the flat buffer of the largest slot, the N-1 peer
+buffers and the statistics.  Every tensor is a view at its dense offset in registration order, so a kernel sees
+a handful of long contiguous streams rather than hundreds of separate allocations.
 """
 from __future__ import annotations
 
@@ -19,8 +20,9 @@ from . import workloads as W
 
 class DeviceReplica:
     def __init__(self, w: W.Workload, device: int = 0, options: Optional[Dict[str, int]] = None, arena_offset: int = 0,
-                 grad_dtype: Optional[str] = None):
-        """arena_offset: elements skipped at the start of every arena (tests use it to break 16-byte alignment)."""
+                 grad_dtype: Optional[str] = None, policy: Optional[str] = None, n_peers: Optional[int] = None):
+        """Schedules, allocates, registers.  arena_offset: elements skipped at the start of every arena (tests use
+        it to break 16-byte alignment).  policy: schedule policy (default: the workload's)."""
         self.w = w
         self.dev = torch.device("cuda", device)
         torch.cuda.set_device(self.dev)
@@ -31,45 +33,60 @@ class DeviceReplica:
         self.bf16 = w.param_dtype == "bf16"
         self.grad_bf16 = (grad_dtype or ("bf16" if self.bf16 else "f32")) == "bf16"
         self.adam = w.optimizer == "adamw"
-        o = arena_offset
-        self.a_sync = torch.zeros(P + o, dtype=torch.float32, device=self.dev)
-        self.a_model = torch.zeros(P + o, dtype=torch.bfloat16, device=self.dev) if self.bf16 else None
-        self.a_grad = torch.zeros(P + o, dtype=torch.bfloat16 if self.grad_bf16 else torch.float32, device=self.dev)
-        self.a_s0 = torch.zeros(P + o, dtype=torch.float32, device=self.dev)
-        self.a_s1 = torch.zeros(P + o, dtype=torch.float32, device=self.dev) if self.adam else None
-        self.offsets = np.concatenate([[0], np.cumsum([t.numel for t in w.tensors])]).astype(np.int64) + o
-
-        def views(a):
-            return None if a is None else [a[int(self.offsets[i]): int(self.offsets[i]) + t.numel] for i, t in enumerate(w.tensors)]
-
-        self.sync, self.model, self.grad = views(self.a_sync), views(self.a_model), views(self.a_grad)
-        self.s0, self.s1 = views(self.a_s0), views(self.a_s1)
         self.layer_of = [t.layer for t in w.tensors]
         self.numel = [t.numel for t in w.tensors]
-        self.ctx.ddp_register_model(w.n_layers, self.layer_of, self.numel, B.DDP_BF16 if self.bf16 else B.DDP_F32,
-                                    B.DDP_BF16 if self.grad_bf16 else B.DDP_F32, self.sync, self.model, self.grad, self.s0, self.s1)
-        self.sets: List[List[int]] = []
-        self.flat: Optional[torch.Tensor] = None
-        self.peers: List[torch.Tensor] = []
-        self.stats: Optional[torch.Tensor] = None
 
-    # -- schedule -------------------------------------------------------------------------------------------
-    def set_schedule(self, policy: Optional[str] = None) -> None:
-        w = self.w
+        # schedule first (CPU): the slot sizes decide how much flat / peer space the slab needs
         fp, bp, comm = W.synthetic_times(w)
         _, sp, sl, self.cost = B.ddp_schedule(policy or w.policy, w.n_layers, w.period, fp, bp, comm)
         self.set_ptr, self.set_layers = sp, sl
         self.sets = B.sets_from_csr(sp, sl)
+        lay = w.layer_numel()
+        smax = max(max(sum(lay[l] for l in S) for S in self.sets), 4)
+        n_peers = w.n_replicas - 1 if n_peers is None else n_peers
+        max_layers = max(len(S) for S in self.sets)
+
+        # one slab for everything this worker owns on the device; every region starts on a 2 MiB boundary
+        o = arena_offset
+        regions = [("sync", torch.float32, P + o), ("s0", torch.float32, P + o)]
+        if self.adam:
+            regions.append(("s1", torch.float32, P + o))
+        regions.append(("grad", torch.bfloat16 if self.grad_bf16 else torch.float32, P + o))
+        if self.bf16:
+            regions.append(("model", torch.bfloat16, P + o))
+        regions.append(("flat", torch.float32, smax))
+        regions += [(f"peer{k}", torch.float32, smax) for k in range(n_peers)]
+        regions.append(("stats", torch.float64, 2 * max_layers + 2))
+        ALIGN = 2 << 20
+        pos, place = 0, {}
+        for name, dt, n in regions:
+            nbytes = n * torch.empty((), dtype=dt).element_size()
+            place[name] = (pos, nbytes, dt)
+            pos += (nbytes + ALIGN - 1) // ALIGN * ALIGN
+        self.slab = torch.zeros(pos, dtype=torch.uint8, device=self.dev)
+
+        def region(name):
+            if name not in place:
+                return None
+            start, nbytes, dt = place[name]
+            return self.slab[start:start + nbytes].view(dt)
+
+        self.a_sync, self.a_s0, self.a_s1 = region("sync"), region("s0"), region("s1")
+        self.a_grad, self.a_model = region("grad"), region("model")
+        self.flat, self.stats = region("flat"), region("stats")
+        self.peers = [region(f"peer{k}") for k in range(n_peers)]
+        self.offsets = np.concatenate([[0], np.cumsum(self.numel)]).astype(np.int64) + o
+
+        def views(a):
+            return None if a is None else [a[int(self.offsets[i]): int(self.offsets[i]) + n] for i, n in enumerate(self.numel)]
+
+        self.sync, self.model, self.grad = views(self.a_sync), views(self.a_model), views(self.a_grad)
+        self.s0, self.s1 = views(self.a_s0), views(self.a_s1)
+        self.ctx.ddp_register_model(w.n_layers, self.layer_of, self.numel, B.DDP_BF16 if self.bf16 else B.DDP_F32,
+                                    B.DDP_BF16 if self.grad_bf16 else B.DDP_F32, self.sync, self.model, self.grad, self.s0, self.s1)
         self.ctx.ddp_set_schedule(sp, sl)
         self.slot_numel = [self.ctx.ddp_slot_numel(s) for s in range(len(self.sets))]
-        smax = max(max(self.slot_numel), 4)
-        self.flat = torch.zeros(smax, dtype=torch.float32, device=self.dev)
-        self.stats = torch.zeros(2 * max(len(S) for S in self.sets) + 2, dtype=torch.float64, device=self.dev)
-
-    def alloc_peers(self, n_peers: Optional[int] = None) -> None:
-        n = self.w.n_replicas - 1 if n_peers is None else n_peers
-        smax = max(max(self.slot_numel), 4)
-        self.peers = [torch.zeros(smax, dtype=torch.float32, device=self.dev) for _ in range(n)]
+        assert max(max(self.slot_numel), 4) == smax
 
     # -- seeded inputs (harness work, outside any timed region) ---------------------------------------------
     def init_params(self) -> None:

@@ -67,10 +67,8 @@ def run_trajectory(oracle, w, policy=None, iters=None, arena_offset=0, options=N
     _need_gpu()
     oracle.set_threads(threads)
     iters = iters or w.iterations
-    rep = DeviceReplica(w, 0, options=options, arena_offset=arena_offset, grad_dtype=grad_dtype)
+    rep = DeviceReplica(w, 0, options=options, arena_offset=arena_offset, grad_dtype=grad_dtype, policy=policy)
     rep.init_params()
-    rep.set_schedule(policy)
-    rep.alloc_peers()
     N, H = w.n_replicas, w.period
     fp, bp, comm = W.synthetic_times(w)
     policy = policy or w.policy
@@ -225,10 +223,8 @@ def test_determinism_two_runs_same_bits(oracle):
     w = W.small_llama()
     snaps = []
     for _ in range(2):
-        rep = DeviceReplica(w, 0)
+        rep = DeviceReplica(w, 0, policy="opt")
         rep.init_params()
-        rep.set_schedule("opt")
-        rep.alloc_peers()
         stats_all = []
         for r in range(8):
             rep.fill_grads(r)
