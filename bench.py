@@ -28,8 +28,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 
 # HBM bytes per launch of the update kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what
-# the same counters read for a plain copy of known size; None until measured for the workload.
-MEASURED_TRAFFIC_BYTES = {}
+# the same counters read for a plain copy of known size (profiles/llama2_7b_step_kernels.txt); None if not measured.
+MEASURED_TRAFFIC_BYTES = {"llama2_7b": 188.781e9}
 
 
 def algorithmic_bytes(w, S: int):
@@ -97,6 +97,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stats", action="store_true", help="skip the per-layer statistics in the average")
     ap.add_argument("--option", action="append", default=[], help="library option name=value (repeatable)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run 4 plain elementwise copies of 1 GiB (torch.add(src, 0, out=dst)) before the timed region, "
+                         "as the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (peers are staged in HBM; there are no collectives). "
@@ -120,6 +123,14 @@ def main() -> int:
     torch.cuda.synchronize()
     rep.fill_peers_from(rep.flat, 0, rep.flat.numel())
     torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        src = torch.full((1 << 28,), 1.5, dtype=torch.float32, device=rep.dev)      # 1 GiB read, 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            torch.add(src, 0.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     H = len(rep.sets)
     with_stats = not args.no_stats
