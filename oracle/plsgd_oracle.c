@@ -118,19 +118,22 @@ void orc_mean(int N, const float *const *x, int64_t n, float *out) {
 
 /* Per-layer divergence and squared norm over flat range [begin, end):
  *   gamma = (1/N) sum_k sum_i (mean[i] - x_k[i])^2,  msq = sum_i mean[i]^2.
- * Each difference is formed in fp32 (the precision the replicas are held in), squares and sums are fp64. */
+ * Each difference is formed in fp32 (the precision the replicas are held in); its square is exact in fp64.
+ * The running sums are kept in extended precision (x87 long double, 64-bit mantissa): a plain fp64 running sum
+ * over the 5e8 terms of a 65 M-element layer drifts by 5e-10 relative, which would make the oracle the less
+ * accurate side of the comparison.  The result is rounded to fp64 once at the end. */
 void orc_layer_stats(int N, const float *const *x, const float *mean, int64_t begin, int64_t end, double *gamma,
                      double *msq) {
-    double g = 0.0, m = 0.0;
+    long double g = 0.0L, m = 0.0L;
     for (int64_t i = begin; i < end; ++i) {
         for (int k = 0; k < N; ++k) {
             float d = mean[i] - x[k][i];
-            g += (double)d * (double)d;
+            g += (long double)((double)d * (double)d);
         }
-        m += (double)mean[i] * (double)mean[i];
+        m += (long double)((double)mean[i] * (double)mean[i]);
     }
-    *gamma = g / (double)N;
-    *msq = m;
+    *gamma = (double)(g / (long double)N);
+    *msq = (double)m;
 }
 
 /* ------------------------------------------------------------------------------------------------------ */

@@ -20,9 +20,11 @@ from . import workloads as W
 
 class DeviceReplica:
     def __init__(self, w: W.Workload, device: int = 0, options: Optional[Dict[str, int]] = None, arena_offset: int = 0,
-                 grad_dtype: Optional[str] = None, policy: Optional[str] = None, n_peers: Optional[int] = None):
+                 grad_dtype: Optional[str] = None, policy: Optional[str] = None, n_peers: Optional[int] = None,
+                 region_skew: int = 0):
         """Schedules, allocates, registers.  arena_offset: elements skipped at the start of every arena (tests use
-        it to break 16-byte alignment).  policy: schedule policy (default: the workload's)."""
+        it to break 16-byte alignment).  policy: schedule policy (default: the workload's).  region_skew: extra bytes
+        (multiple of 256) by which each successive region of the slab is shifted off its 2 MiB boundary."""
         self.w = w
         self.dev = torch.device("cuda", device)
         torch.cuda.set_device(self.dev)
@@ -59,10 +61,11 @@ class DeviceReplica:
         regions.append(("stats", torch.float64, 2 * max_layers + 2))
         ALIGN = 2 << 20
         pos, place = 0, {}
-        for name, dt, n in regions:
+        for j, (name, dt, n) in enumerate(regions):
             nbytes = n * torch.empty((), dtype=dt).element_size()
-            place[name] = (pos, nbytes, dt)
+            place[name] = (pos + j * region_skew, nbytes, dt)
             pos += (nbytes + ALIGN - 1) // ALIGN * ALIGN
+        pos += len(regions) * region_skew
         self.slab = torch.zeros(pos, dtype=torch.uint8, device=self.dev)
 
         def region(name):

@@ -1,0 +1,158 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times.
+
+TinyLlama-1.1B: the whole 16-iteration trajectory, every element, against the oracle.
+Llama-2-7B (8 iterations) and Llama-3-8B (N = 16, ragged schedule): the oracle carries ~1.1 M sampled parameters
+(random positions plus every tensor boundary and chunk boundaries) through the whole trajectory, one by one;
+on top of that every element is checked on the device against independent gathers / sequential torch sums
+(pack, unpack and the average are exact, so they must agree bit for bit at any size).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_11058_amd import workloads as W
+from test_gpu_parity import _bits, _need_gpu, _np, assert_bf16_within_one_ulp, assert_close_fp32, run_trajectory
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.timeout(1500)
+def test_tinyllama_full_trajectory(oracle):
+    t = run_trajectory(oracle, W.tinyllama_1b(), check_every=4)
+    assert t.frac() == 1.0
+
+
+def _sample_positions(rep, n_random, seed):
+    P = int(rep.offsets[-1] - rep.offsets[0])
+    rng = np.random.default_rng(seed)
+    pos = [rng.integers(0, P, n_random, dtype=np.int64)]
+    starts = rep.offsets[:-1] - rep.offsets[0]
+    for d in range(-4, 5):                                   # both sides of every tensor boundary
+        pos.append(np.clip(starts + d, 0, P - 1))
+    big = np.argsort(rep.numel)[-6:]                          # chunk boundaries inside the largest tensors
+    for t in big:
+        k = rng.integers(1, max(2, rep.numel[t] // 8192), 64)
+        for d in range(-2, 3):
+            pos.append(np.clip(starts[t] + k * 8192 + d, 0, P - 1))
+    pos.append(np.array([0, 1, 2, 3, P - 4, P - 3, P - 2, P - 1]))
+    return np.unique(np.concatenate(pos)) + int(rep.offsets[0])
+
+
+def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000):
+    from paper_2502_11058_amd.harness import DeviceReplica
+    _need_gpu()
+    oracle.set_threads(16)
+    free, total_mem = torch.cuda.mem_get_info()
+    rep = DeviceReplica(w, 0)
+    rep.init_params()
+    N, H = w.n_replicas, w.period
+    dev = rep.dev
+    gi_host = _sample_positions(rep, n_random, 7)
+    gi = torch.from_numpy(gi_host).to(dev)
+    tensor_of = np.searchsorted(rep.offsets, gi_host, side="right") - 1
+    p_s = _np(rep.a_sync[gi])
+    m_s, v_s = np.zeros_like(p_s), np.zeros_like(p_s)
+    model_s = oracle.bf16_rne(p_s)
+    assert np.array_equal(_np(rep.a_model[gi]), model_s)
+    inv_n = torch.tensor(1.0 / N, dtype=torch.float32, device=dev)
+    n_exact = n_total = 0
+
+    for r in range(iters):
+        slot, S, rank = r % H, rep.sets[r % H], r % N
+        off, order_t, total = oracle.slot_offsets(rep.layer_of, rep.numel, S)
+        tid, toff, lid, lbeg = rep.ctx.ddp_slot_layout(slot)
+        assert rep.ctx.ddp_slot_numel(slot) == total and tid.tolist() == order_t.tolist()
+        assert toff.tolist() == [int(off[t]) for t in order_t] and lid.tolist() == list(S)
+        # which samples are scheduled, and where they sit in the flat buffer
+        sel_host = off[tensor_of] >= 0
+        fi_host = (off[tensor_of] + (gi_host - rep.offsets[tensor_of]))[sel_host]
+        fi, gsel = torch.from_numpy(fi_host).to(dev), torch.from_numpy(gi_host[sel_host]).to(dev)
+        rep.fill_grads(r)
+        g_s = _np(rep.a_grad[gi])
+        base = torch.cat([rep.sync[t] for t in order_t])       # independent gather (harness), the peers' base
+        rep.fill_peers_from(base, r, total)
+        # pack: every element against the gather
+        rep.flat.fill_(float("nan"))
+        rep.ctx.ddp_pack(slot, rep.flat)
+        assert torch.equal(rep.flat[:total].view(torch.int32), base.view(torch.int32)), f"pack r={r}"
+        x_s = [_np(p[fi]) for p in rep.peers]
+        loc_s = _np(base[fi])
+        reps_s = x_s[:rank] + [loc_s] + x_s[rank:]
+        # sequential torch sum in rank order: an independent fp32 evaluation of every element
+        seq = rep.peers[:rank] + [base] + rep.peers[rank:]
+        acc = seq[0][:total].clone()
+        for k in range(1, N):
+            acc.add_(seq[k][:total])
+        acc.mul_(inv_n)
+        del base, seq
+        rep.stats.fill_(-1.0)
+        rep.ctx.ddp_partial_average(slot, rep.flat, rep.peers, N, rank, rep.flat, rep.stats)
+        assert torch.equal(rep.flat[:total].view(torch.int32), acc.view(torch.int32)), f"mean (all elements) r={r}"
+        mean_s = oracle.mean(reps_s)
+        assert np.array_equal(_bits(_np(rep.flat[fi])), _bits(mean_s)), f"mean (oracle samples) r={r}"
+        # statistics: the oracle on one whole layer, a device-side fp64 evaluation on all layers
+        st = _np(rep.stats)
+        sizes = [int(lbeg[i + 1] - lbeg[i]) for i in range(len(S))]
+        for i in range(len(S)):
+            b, e = int(lbeg[i]), int(lbeg[i + 1])
+            g64 = torch.zeros((), dtype=torch.float64, device=dev)
+            for k in range(N):
+                if k != rank:
+                    xk = rep.peers[k - (k > rank)][b:e]
+                else:       # averaged in place: the local values are still in the model tensors until unpack
+                    xk = torch.cat([rep.sync[t] for t in order_t if rep.layer_of[t] == S[i]])
+                d = (rep.flat[b:e] - xk).double()
+                g64 += (d * d).sum()
+            m64 = (rep.flat[b:e].double() ** 2).sum()
+            assert st[2 * i] == pytest.approx(float(g64) / N, rel=1e-9), f"gamma (device fp64) r={r} layer {S[i]}"
+            assert st[2 * i + 1] == pytest.approx(float(m64), rel=1e-9), f"msq (device fp64) r={r} layer {S[i]}"
+        i = int(np.argmin(sizes))
+        if sizes[i] <= stats_layer_cap:
+            b, e = int(lbeg[i]), int(lbeg[i + 1])
+            loc = _np(torch.cat([rep.sync[t] for t in order_t if rep.layer_of[t] == S[i]]))
+            xs = [_np(p[b:e]) for p in rep.peers]
+            layer_reps = xs[:rank] + [loc] + xs[rank:]
+            g, m = oracle.layer_stats(layer_reps, _np(rep.flat[b:e]), 0, e - b)
+            assert st[2 * i] == pytest.approx(g, rel=1e-10), f"gamma (oracle) r={r} layer {S[i]}"
+            assert st[2 * i + 1] == pytest.approx(m, rel=1e-10), f"msq (oracle) r={r} layer {S[i]}"
+            del loc, xs, layer_reps
+        # unpack: every scheduled tensor equals its flat range, its model copy the bf16 rounding; others untouched
+        unsched_before = _np(rep.a_sync[gi])[~sel_host]
+        rep.ctx.ddp_unpack(slot, rep.flat)
+        for t in order_t:
+            assert torch.equal(rep.sync[t].view(torch.int32), rep.flat[int(off[t]): int(off[t]) + rep.numel[t]].view(torch.int32)), f"unpack r={r} t={t}"
+        assert torch.equal(rep.a_model[gsel].view(torch.int16).cpu(), torch.from_numpy(oracle.bf16_rne(mean_s).view(np.int16))), f"model copy r={r}"
+        assert np.array_equal(_bits(_np(rep.a_sync[gi])[~sel_host]), _bits(unsched_before)), f"unscheduled tensors moved r={r}"
+        # the oracle's carried samples take the same step
+        p_s[sel_host] = mean_s
+        model_s[sel_host] = oracle.bf16_rne(mean_s)
+        rep.ctx.ddp_local_update(rep.opt_struct(r + 1))
+        oracle.adamw(p_s, g_s, m_s, v_s, model_s, w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, r + 1)
+        gp, gm, gv = _np(rep.a_sync[gi]), _np(rep.a_s0[gi]), _np(rep.a_s1[gi])
+        assert_close_fp32(gp, p_s, f"param r={r}", 1e-9)
+        assert_close_fp32(gm, m_s, f"m r={r}", 1e-12)
+        assert_close_fp32(gv, v_s, f"v r={r}", 1e-16)
+        assert_bf16_within_one_ulp(_np(rep.a_model[gi]), model_s, f"model r={r}")
+        for a, b_ in ((gp, p_s), (gm, m_s), (gv, v_s)):
+            n_total += a.size
+            n_exact += int((_bits(a) == _bits(b_)).sum())
+        print(f"[{w.name}] r={r} slot {slot} ({total} elements, {len(S)} layers) ok", flush=True)
+    print(f"[{w.name}] {gi_host.size} sampled parameters, optimizer state bit-identical in {100.0 * n_exact / n_total:.4f}%")
+    rep.close()
+    return n_exact / n_total
+
+
+@pytest.mark.timeout(1500)
+def test_llama2_7b_sampled_trajectory(oracle):
+    assert run_sampled(oracle, W.llama2_7b(), iters=8) == 1.0
+
+
+@pytest.mark.timeout(1500)
+def test_llama3_8b_ragged_schedule_sampled_trajectory(oracle):
+    w = W.llama3_8b()
+    free, total = torch.cuda.mem_get_info() if torch.cuda.is_available() else (0, 0)
+    _need_gpu()
+    need = (16 * w.n_params + 4 * 17 * 1_834_000_000 + 4 * 2 * 1_834_000_000) * 1.02
+    if free < need:
+        pytest.skip(f"needs {need / 1e9:.0f} GB of free HBM, {free / 1e9:.0f} GB available")
+    assert run_sampled(oracle, w, iters=8) == 1.0

@@ -112,3 +112,18 @@ def test_gamma_expectation_for_drifted_peers(oracle):
     m = oracle.mean(reps)
     g, _ = oracle.layer_stats(reps, m, 0, n)
     assert g == pytest.approx(n * s * s * (N - 1) ** 2 / N ** 2, rel=0.02)
+
+
+def test_stats_running_sums_do_not_drift(oracle):
+    # Gamma is a mathematical sum (Sec. 3.4); the oracle's accumulators are extended precision so that 3e7 terms
+    # agree with numpy's pairwise fp64 sum to 1e-12 (a plain fp64 running sum is off by ~3e-11 here and by
+    # 5e-10 at the size of a 65 M-element layer)
+    N, n = 8, 4_000_000
+    rng = np.random.default_rng(60)
+    loc = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    reps = [loc] + [loc + (rng.standard_normal(n) * 1e-4).astype(np.float32) for _ in range(N - 1)]
+    m = oracle.mean(reps)
+    g, msq = oracle.layer_stats(reps, m, 0, n)
+    d = (m[None, :] - np.stack(reps)).astype(np.float64)
+    assert g == pytest.approx(float((d * d).sum() / N), rel=1e-12)
+    assert msq == pytest.approx(float((m.astype(np.float64) ** 2).sum()), rel=1e-12)
