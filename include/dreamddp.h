@@ -89,6 +89,30 @@ int ddp_schedule_cost(int L, int H, const int64_t *t_bp_ns, const int64_t *t_com
 /* Size of Algorithm 2's solution set Omega for the instance (Sec. 3.3, complexity analysis).  Host pointers. */
 int ddp_schedule_alg2_solutions(int L, int H, const int64_t *t_bp_ns, const int64_t *t_comm_ns, int64_t *out_count);
 
+/* Sec. 3.4 "filling the bubble time", Eq. (12), Algorithm 2 lines 3-6.  Input: a schedule that is a cut of the
+ * BP-ordered layers (as ddp_schedule writes for ENP, FULL, OPT, ALG2).  Every set additionally takes the longest
+ * prefix L-1, L-2, ..., l of the BP order that is disjoint from it and keeps
+ *     max(rem(h0), t_COMM(set) + t_COMM(prefix)) <= max(rem(h0), t_COMM(set)),
+ * rem(h0) = backward time left after the set's first layer (for an empty set: after the top layer), t_COMM = plain
+ * sums.  Layers of the prefix are then synchronised more than once per period.
+ *   out_set_ptr [H+1], out_set_layers [capacity L*H]: CSR of the filled schedule, each set in BP order (the
+ *   prefix first); out_extra [H], nullable: number of layers added per set.  Host pointers.
+ * Errors: DDP_EINVAL (arguments, negative times), DDP_ESCHED (input is not a cut). */
+int ddp_schedule_fill_bubbles(int L, int H, const int64_t *t_bp_ns, const int64_t *t_comm_ns, const int32_t *set_ptr,
+                              const int32_t *set_layers, int32_t *out_set_ptr, int32_t *out_set_layers, int32_t *out_extra);
+
+/* Eq. (7): wall-clock model of one synchronisation period with communication timestamps.  Within an iteration
+ * the communication of a scheduled layer starts when that layer's backward is done and the previous
+ * communication has ended (tau recursion); the iteration lasts forward + max(end of backward, end of the last
+ * communication).  Sets may be any distinct layers listed in BP order (descending id), e.g. a filled schedule.
+ *   t_fp_ns nullable (then 0).  out_iter_ns [H]: time of each iteration; out_exposed_ns [H], nullable:
+ *   communication time not hidden by the backward pass; out_period_ns, nullable: sum over the H iterations
+ *   (T_P-LSGD of Eq. (7) for R = H).  Host pointers.
+ * Errors: DDP_EINVAL, DDP_ESCHED (set not in BP order, layer out of range). */
+int ddp_schedule_time_model(int L, int H, const int64_t *t_fp_ns, const int64_t *t_bp_ns, const int64_t *t_comm_ns,
+                            const int32_t *set_ptr, const int32_t *set_layers, int64_t *out_iter_ns, int64_t *out_exposed_ns,
+                            int64_t *out_period_ns);
+
 /* Context on GPU `device` (HIP ordinal).  The device must be the caller's current device in later calls. */
 int ddp_create(ddp_ctx **out, int device);
 int ddp_destroy(ddp_ctx *ctx);

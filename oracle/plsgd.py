@@ -39,6 +39,8 @@ def lib():
         _lib.orc_sched_cost.restype = C.c_int64
         _lib.orc_sched_brute.restype = C.c_int64
         _lib.orc_sched_alg2.restype = C.c_int64
+        _lib.orc_eq7_summand.restype = C.c_int64
+        _lib.orc_iteration_timeline.restype = C.c_int64
     return _lib
 
 
@@ -204,6 +206,47 @@ def sched_enp(L: int, H: int) -> List[int]:
     s = np.zeros(H, dtype=np.int32)
     lib().orc_sched_enp(L, H, _p(s))
     return s.tolist()
+
+
+def eq7_summand(bp: Sequence[int], comm: Sequence[int], pos: int, size: int) -> int:
+    """One summand of Eq. (7) as printed, for the contiguous set at BP positions [pos, pos+size)."""
+    b = np.asarray(bp, dtype=np.int64)
+    c = np.asarray(comm, dtype=np.int64)
+    return int(lib().orc_eq7_summand(len(b), _p(b), _p(c), pos, size))
+
+
+def iteration_timeline(bp: Sequence[int], comm: Sequence[int], layers: Sequence[int]) -> Tuple[int, int]:
+    """(end of backward + communication, exposed communication) of one iteration that synchronises `layers`."""
+    b = np.asarray(bp, dtype=np.int64)
+    c = np.asarray(comm, dtype=np.int64)
+    ls = np.asarray(layers, dtype=np.int32)
+    ex = C.c_int64(0)
+    t = lib().orc_iteration_timeline(len(b), _p(b), _p(c), len(ls), _p(ls), C.byref(ex))
+    return int(t), int(ex.value)
+
+
+def time_model(fp: Sequence[int], bp: Sequence[int], comm: Sequence[int], sets: Sequence[Sequence[int]]) -> Tuple[List[int], List[int], int]:
+    """Eq. (7) for one period: per-iteration time (forward + backward/communication), exposed communication per
+    iteration, and the period total."""
+    f = int(np.sum(np.asarray(fp, dtype=np.int64)))
+    it, ex = [], []
+    for S in sets:
+        t, e = iteration_timeline(bp, comm, S)
+        it.append(f + t)
+        ex.append(e)
+    return it, ex, int(sum(it))
+
+
+def fill_bubbles(bp: Sequence[int], comm: Sequence[int], sizes: Sequence[int]) -> Tuple[List[int], List[List[int]]]:
+    """Eq. (12): (number of top layers added per set, the resulting sets in BP order)."""
+    b = np.asarray(bp, dtype=np.int64)
+    c = np.asarray(comm, dtype=np.int64)
+    s = np.asarray(sizes, dtype=np.int32)
+    extra = np.zeros(len(s), dtype=np.int32)
+    lib().orc_fill_bubbles(len(b), len(s), _p(b), _p(c), _p(s), _p(extra))
+    L = len(b)
+    base = sets_from_sizes(L, sizes)
+    return extra.tolist(), [[L - 1 - j for j in range(e)] + S for e, S in zip(extra.tolist(), base)]
 
 
 def sets_from_sizes(L: int, sizes: Sequence[int]) -> List[List[int]]:

@@ -349,3 +349,81 @@ int64_t orc_sched_alg2(int L, int H, const int64_t *bp, const int64_t *comm, int
 void orc_sched_enp(int L, int H, int32_t *sizes) {
     for (int h = 0; h < H; ++h) sizes[h] = L / H + (h < L % H ? 1 : 0);
 }
+
+/* ------------------------------------------------------------------------------------------------------ */
+/* Eq. (7): wall-clock model with communication timestamps; Sec. 3.4 / Eq. (12): filling the bubbles       */
+/* ------------------------------------------------------------------------------------------------------ */
+
+/* One summand of Eq. (7) as printed, for the set that covers BP positions [pos, pos+size) (position j is layer
+ * L-1-j): t_BP(sets before) + t_BP(h0) + max( t_BP(sets h..H) - t_BP(h0), t_COMM(L_h) ), where
+ *   tau(h_0) = t_BP(h_0),  tau(h_j) = max( t_BP(h_0..h_j), tau(h_{j-1}) + t_COMM(h_{j-1}) ),
+ *   t_COMM(L_h) = tau(h_last) + t_COMM(h_last) - tau(h_0).
+ * An empty set costs one whole backward pass. */
+int64_t orc_eq7_summand(int L, const int64_t *bp, const int64_t *comm, int pos, int size) {
+    int64_t before = 0, from = 0;
+    for (int j = 0; j < pos; ++j) before += bp[L - 1 - j];
+    for (int j = pos; j < L; ++j) from += bp[L - 1 - j];
+    if (size == 0) return before + from;
+    int h0 = L - 1 - pos;
+    int64_t bp_run = bp[h0]; /* t_BP(h_0..h_j), running */
+    int64_t tau0 = bp_run, tau = tau0;
+    for (int j = 1; j < size; ++j) {
+        int prev = L - 1 - (pos + j - 1), cur = L - 1 - (pos + j);
+        bp_run += bp[cur];
+        int64_t after_prev = tau + comm[prev];
+        tau = bp_run > after_prev ? bp_run : after_prev;
+    }
+    int last = L - 1 - (pos + size - 1);
+    int64_t span = tau + comm[last] - tau0;
+    int64_t rem = from - bp[h0];
+    return before + bp[h0] + (rem > span ? rem : span);
+}
+
+/* The same model for an arbitrary set given as layer ids in BP order (descending), on the time line of one
+ * iteration's backward pass: layer l finishes its backward at done(l) = sum of bp over layers >= l; a layer's
+ * communication starts when its backward is done and the previous communication has ended.  Returns the end of
+ * backward-plus-communication; *exposed = how far the communication runs past the end of the backward pass. */
+int64_t orc_iteration_timeline(int L, const int64_t *bp, const int64_t *comm, int n, const int32_t *layers, int64_t *exposed) {
+    int64_t total = 0;
+    for (int l = 0; l < L; ++l) total += bp[l];
+    int64_t comm_end = 0;
+    for (int j = 0; j < n; ++j) {
+        int l = layers[j];
+        int64_t done = 0;
+        for (int k = l; k < L; ++k) done += bp[k];
+        int64_t start = done > comm_end ? done : comm_end;
+        comm_end = start + comm[l];
+    }
+    if (exposed) *exposed = comm_end > total ? comm_end - total : 0;
+    return comm_end > total ? comm_end : total;
+}
+
+/* Sec. 3.4, Eq. (12), Algorithm 2 lines 3-6: after scheduling, set h additionally synchronises the top layers
+ * L-1, L-2, ..., l (a prefix of the BP order, disjoint from the set) as long as
+ *   max( rem(h0), t_COMM(L_h) + t_COMM(extra) ) <= max( rem(h0), t_COMM(L_h) ),
+ * with plain sums for t_COMM and h0 the set's own first layer.  The largest such prefix is taken.  An empty set
+ * has no h0 of its own: its first layer would be the top layer, so rem is taken after the top layer's backward.
+ * sizes[] describes the cut; extra[h] receives the number of top layers added to set h. */
+void orc_fill_bubbles(int L, int H, const int64_t *bp, const int64_t *comm, const int32_t *sizes, int32_t *extra) {
+    int pos = 0;
+    for (int h = 0; h < H; ++h) {
+        int limit = sizes[h] ? pos : L;          /* the prefix must stay disjoint from the set */
+        int h0 = sizes[h] ? L - 1 - pos : L - 1;
+        int64_t rem = 0;
+        for (int l = 0; l < h0; ++l) rem += bp[l];
+        int64_t c_set = 0;
+        for (int j = pos; j < pos + sizes[h]; ++j) c_set += comm[L - 1 - j];
+        int64_t budget = rem > c_set ? rem : c_set;  /* right-hand side of Eq. (12) */
+        int e = 0;
+        int64_t c_extra = 0;
+        while (e < limit) {
+            int64_t with = c_set + c_extra + comm[L - 1 - e];
+            int64_t lhs = rem > with ? rem : with;
+            if (lhs > budget) break;
+            c_extra += comm[L - 1 - e];
+            ++e;
+        }
+        extra[h] = e;
+        pos += sizes[h];
+    }
+}

@@ -22,7 +22,7 @@ STATUS = {0: "DDP_OK", 1: "DDP_EINVAL", 2: "DDP_ESHAPE", 3: "DDP_EALIGN", 4: "DD
           7: "DDP_ESTATE"}
 
 EXPORTS = [
-    "ddp_schedule", "ddp_schedule_cost", "ddp_schedule_alg2_solutions", "ddp_create", "ddp_destroy", "ddp_set_option",
+    "ddp_schedule", "ddp_schedule_cost", "ddp_schedule_alg2_solutions", "ddp_schedule_fill_bubbles", "ddp_schedule_time_model", "ddp_create", "ddp_destroy", "ddp_set_option",
     "ddp_register_model", "ddp_set_schedule", "ddp_slot_numel", "ddp_slot_num_layers", "ddp_slot_num_tensors",
     "ddp_slot_layout", "ddp_pack", "ddp_partial_average", "ddp_unpack", "ddp_local_update", "ddp_last_error",
 ]
@@ -71,6 +71,8 @@ def lib():
         l.ddp_schedule.argtypes = [C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7
         l.ddp_schedule_cost.argtypes = [C.c_int, C.c_int] + [C.c_void_p] * 5
         l.ddp_schedule_alg2_solutions.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.ddp_schedule_fill_bubbles.argtypes = [C.c_int, C.c_int] + [C.c_void_p] * 7
+        l.ddp_schedule_time_model.argtypes = [C.c_int, C.c_int] + [C.c_void_p] * 8
         _lib = l
     return _lib
 
@@ -124,6 +126,41 @@ def ddp_schedule_alg2_solutions(t_bp, t_comm, H: int) -> int:
     n = C.c_int64(0)
     _check(lib().ddp_schedule_alg2_solutions(len(bp), H, bp.ctypes.data, cm.ctypes.data, C.addressof(n)))
     return int(n.value)
+
+
+def ddp_schedule_fill_bubbles(t_bp, t_comm, set_ptr, set_layers) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """-> (set_ptr[H+1], set_layers, extra[H]) of the schedule after Eq. (12)'s bubble filling."""
+    bp, cm, sp, sl = _i64(t_bp), _i64(t_comm), _i32(set_ptr), _i32(set_layers)
+    L, H = len(bp), len(sp) - 1
+    if len(sl) == 0:
+        sl = np.zeros(1, dtype=np.int32)
+    osp = np.zeros(H + 1, dtype=np.int32)
+    osl = np.zeros(max(L * H, 1), dtype=np.int32)
+    ext = np.zeros(H, dtype=np.int32)
+    _check(lib().ddp_schedule_fill_bubbles(L, H, bp.ctypes.data, cm.ctypes.data, sp.ctypes.data, sl.ctypes.data,
+                                           osp.ctypes.data, osl.ctypes.data, ext.ctypes.data))
+    return osp, osl[: osp[H]].copy(), ext
+
+
+def ddp_schedule_time_model(t_fp, t_bp, t_comm, set_ptr, set_layers) -> Tuple[np.ndarray, np.ndarray, int]:
+    """-> (iteration time [H], exposed communication [H], period total) under Eq. (7)."""
+    fp = None if t_fp is None else _i64(t_fp)
+    bp, cm, sp, sl = _i64(t_bp), _i64(t_comm), _i32(set_ptr), _i32(set_layers)
+    H = len(sp) - 1
+    if len(sl) == 0:
+        sl = np.zeros(1, dtype=np.int32)
+    it = np.zeros(H, dtype=np.int64)
+    ex = np.zeros(H, dtype=np.int64)
+    per = C.c_int64(0)
+    _check(lib().ddp_schedule_time_model(len(bp), H, _np_ptr(fp), bp.ctypes.data, cm.ctypes.data, sp.ctypes.data, sl.ctypes.data,
+                                         it.ctypes.data, ex.ctypes.data, C.addressof(per)))
+    return it, ex, int(per.value)
+
+
+def csr_from_sets(sets) -> Tuple[np.ndarray, np.ndarray]:
+    sp = np.cumsum([0] + [len(S) for S in sets]).astype(np.int32)
+    sl = np.asarray([l for S in sets for l in S], dtype=np.int32)
+    return sp, sl
 
 
 def sets_from_csr(set_ptr, set_layers) -> List[List[int]]:

@@ -11,7 +11,7 @@ import pytest
 import torch
 
 from paper_2502_11058_amd import workloads as W
-from test_gpu_parity import _bits, _need_gpu, _np, assert_bf16_within_one_ulp, assert_close_fp32, run_trajectory
+from test_gpu_parity import _bits, _need_gpu, _np, assert_bf16_within_one_ulp, assert_close_fp32, progress, run_trajectory
 
 pytestmark = pytest.mark.gpu
 
@@ -136,8 +136,8 @@ def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000)
         for a, b_ in ((gp, p_s), (gm, m_s), (gv, v_s)):
             n_total += a.size
             n_exact += int((_bits(a) == _bits(b_)).sum())
-        print(f"[{w.name}] r={r} slot {slot} ({total} elements, {len(S)} layers) ok", flush=True)
-    print(f"[{w.name}] {gi_host.size} sampled parameters, optimizer state bit-identical in {100.0 * n_exact / n_total:.4f}%")
+        progress(f"[{w.name}] r={r} slot {slot} ({total} elements, {len(S)} layers) ok")
+    progress(f"[{w.name}] {gi_host.size} sampled parameters, optimizer state bit-identical in {100.0 * n_exact / n_total:.4f}%")
     rep.close()
     return n_exact / n_total
 

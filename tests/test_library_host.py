@@ -129,3 +129,54 @@ def test_schedule_argument_errors():
         assert e.value.code == 1 and len(str(e.value)) > 10
     with pytest.raises(B.DdpError):
         B.ddp_schedule(17, 2, 2, None, [1, 1], [1, 1])
+
+
+def test_fill_bubbles_equals_oracle(oracle):
+    rng = np.random.default_rng(20)
+    for _ in range(800):
+        L, H = int(rng.integers(1, 12)), int(rng.integers(1, 6))
+        bp = rng.integers(0, 30, L)
+        comm = rng.integers(0, 30, L)
+        cuts = sorted(rng.integers(0, L + 1, H - 1).tolist())
+        edges = [0] + cuts + [L]
+        sizes = [edges[i + 1] - edges[i] for i in range(H)]
+        sp, sl = B.csr_from_sets(oracle.sets_from_sizes(L, sizes))
+        osp, osl, extra = B.ddp_schedule_fill_bubbles(bp, comm, sp, sl)
+        e_ref, sets_ref = oracle.fill_bubbles(bp, comm, sizes)
+        assert extra.tolist() == e_ref and B.sets_from_csr(osp, osl) == sets_ref
+    with pytest.raises(B.DdpError) as e:
+        B.ddp_schedule_fill_bubbles([1, 1], [1, 1], [0, 1, 2], [0, 1])
+    assert e.value.code == 6
+
+
+def test_time_model_equals_oracle(oracle):
+    rng = np.random.default_rng(21)
+    for _ in range(800):
+        L, H = int(rng.integers(1, 12)), int(rng.integers(1, 6))
+        fp = rng.integers(0, 10, L)
+        bp = rng.integers(0, 30, L)
+        comm = rng.integers(0, 60, L)
+        # arbitrary subsets in BP order, not only cuts
+        sets = [sorted(rng.choice(L, int(rng.integers(0, L + 1)), replace=False).tolist(), reverse=True) for _ in range(H)]
+        sp, sl = B.csr_from_sets(sets)
+        it, ex, period = B.ddp_schedule_time_model(fp, bp, comm, sp, sl)
+        it_ref, ex_ref, per_ref = oracle.time_model(fp, bp, comm, sets)
+        assert it.tolist() == it_ref and ex.tolist() == ex_ref and period == per_ref
+    with pytest.raises(B.DdpError) as e:
+        B.ddp_schedule_time_model(None, [1, 1], [1, 1], [0, 2], [0, 1])          # ascending ids
+    assert e.value.code == 6
+
+
+@pytest.mark.parametrize("name", ["gpt2_small", "tinyllama_1b", "llama2_7b", "llama3_8b"])
+def test_filled_workload_schedules(oracle, name):
+    w = W.get(name)
+    fp, bp, comm = W.synthetic_times(w)
+    L, H = w.n_layers, w.period
+    for policy in ("enp", "opt", "alg2"):
+        _, sp, sl, _ = B.ddp_schedule(policy, L, H, fp, bp, comm)
+        osp, osl, extra = B.ddp_schedule_fill_bubbles(bp, comm, sp, sl)
+        sizes = [int(sp[i + 1] - sp[i]) for i in range(H)]
+        assert (extra.tolist(), B.sets_from_csr(osp, osl)) == oracle.fill_bubbles(bp, comm, sizes)
+        it0, ex0, per0 = B.ddp_schedule_time_model(fp, bp, comm, sp, sl)
+        it1, ex1, per1 = B.ddp_schedule_time_model(fp, bp, comm, osp, osl)
+        assert (it1.tolist(), ex1.tolist(), per1) == oracle.time_model(fp, bp, comm, B.sets_from_csr(osp, osl))
