@@ -260,7 +260,11 @@ def sets_from_sizes(L: int, sizes: Sequence[int]) -> List[List[int]]:
 
 
 def schedule(policy: str, L: int, H: int, bp: Optional[Sequence[int]] = None, comm: Optional[Sequence[int]] = None) -> List[List[int]]:
-    """Per-slot layer lists.  Slot p is used at 0-based iteration r with r mod H == p."""
+    """Per-slot layer lists.  Slot p is used at 0-based iteration r with r mod H == p.
+    A policy name followed by "+fill" applies Eq. (12)'s bubble filling to the cut."""
+    if policy.endswith("+fill"):
+        base = schedule(policy[:-5], L, H, bp, comm)
+        return fill_bubbles(bp, comm, [len(S) for S in base])[1]
     if policy == "enp":
         return sets_from_sizes(L, sched_enp(L, H))
     if policy == "round_robin":

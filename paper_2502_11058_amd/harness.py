@@ -40,7 +40,10 @@ class DeviceReplica:
 
         # schedule first (CPU): the slot sizes decide how much flat / peer space the slab needs
         fp, bp, comm = W.synthetic_times(w)
-        _, sp, sl, self.cost = B.ddp_schedule(policy or w.policy, w.n_layers, w.period, fp, bp, comm)
+        pol = policy or w.policy
+        _, sp, sl, self.cost = B.ddp_schedule(pol.split("+")[0], w.n_layers, w.period, fp, bp, comm)
+        if pol.endswith("+fill"):      # Sec. 3.4: top layers synchronised more often where the network idles
+            sp, sl, _ = B.ddp_schedule_fill_bubbles(bp, comm, sp, sl)
         self.set_ptr, self.set_layers = sp, sl
         self.sets = B.sets_from_csr(sp, sl)
         lay = w.layer_numel()

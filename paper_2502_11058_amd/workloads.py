@@ -212,7 +212,8 @@ def synthetic_times(w: Workload) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
 
     Recipe: wire bytes of a layer = 4 * numel (fp32 on the wire).  t_comm = bytes / 1 Gbps = 8 ns per byte,
     t_bp = 2 ns per byte, t_fp = 1 ns per byte; with `time_noise` each fwd/bwd time is scaled by an
-    independent U(0.8, 1.2) factor drawn from a numpy generator seeded from the workload."""
+    independent U(0.8, 1.2) factor drawn from a numpy generator seeded from the workload.
+    `w.extra["comm_ns_per_byte"]` overrides the 8 ns per byte (a faster network leaves bubbles to fill)."""
     numel = np.asarray(w.layer_numel(), dtype=np.float64)
     nbytes = 4.0 * numel
     L = len(numel)
@@ -225,5 +226,5 @@ def synthetic_times(w: Workload) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
         ub = np.ones(L)
     t_fp = np.rint(1.0 * nbytes * uf).astype(np.int64)
     t_bp = np.rint(2.0 * nbytes * ub).astype(np.int64)
-    t_comm = np.rint(8.0 * nbytes).astype(np.int64)
+    t_comm = np.rint(float(w.extra.get("comm_ns_per_byte", 8.0)) * nbytes).astype(np.int64)
     return t_fp, t_bp, t_comm

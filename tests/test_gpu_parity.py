@@ -225,6 +225,17 @@ def test_small_llama_alg2_schedule_many_replicas(oracle):
     run_trajectory(oracle, W.small_llama(n_replicas=33, period=5), policy="alg2", iters=10)
 
 
+def test_small_llama_bubble_filled_schedule(oracle):
+    # Sec. 3.4: after filling, top layers sit in several slots; the comm-light synthetic times make filling happen
+    w = W.small_llama()
+    w.extra["comm_ns_per_byte"] = 0.4
+    fp, bp, comm = W.synthetic_times(w)
+    sets = oracle.schedule("enp+fill", w.n_layers, w.period, bp, comm)
+    assert sum(len(S) for S in sets) > w.n_layers          # some layer really is synchronised twice per period
+    t = run_trajectory(oracle, w, policy="enp+fill", iters=8)
+    assert t.frac() == 1.0
+
+
 def test_single_replica_is_identity(oracle):
     w = W.tiny()
     w.n_replicas = 1
