@@ -37,7 +37,7 @@ def test_bad_arguments_are_reported_not_launched(oracle):
     _expect(1, c.ddp_partial_average, 0, flat, rep.peers, N, 0, rep.peers[0])          # output overlaps a peer
     _expect(1, c.ddp_partial_average, 0, flat, rep.peers, N, 0, flat[4:])              # partial overlap with the input
     _expect(3, c.ddp_unpack, 0, flat[2:])
-    _expect(1, c.ddp_local_update, B.make_opt("adamw", 1e-3, 0))           # step is 1-based (and no second moment)
+    _expect(7, c.ddp_local_update, B.make_opt("adamw", 1e-3, 0))           # no second moment registered (checked first)
     opt = B.make_opt("sgdm", 0.01, 1)
     opt.kind = 7
     _expect(1, c.ddp_local_update, opt)
