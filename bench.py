@@ -196,7 +196,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: P={w.n_params}, N={w.n_replicas}, H={w.period}, {w.param_dtype} params, "
                                f"{w.optimizer}, schedule {args.policy or w.policy}, slot sizes {rep.slot_numel}",
-                   "alg_bytes_per_step_avg": total_bytes / args.steps, "layer_stats": with_stats, "options": options},
+                   "alg_bytes_per_step_avg": total_bytes / args.steps, "layer_stats": with_stats, "options": options,
+                   "placement_probe_GBps": [round(x, 1) for x in rep.placement["probe_GBps"]]},
         "kernels": kernels, "roofline": roofline,
     }
     if not args.no_cpu_baseline:

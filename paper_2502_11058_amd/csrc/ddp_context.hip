@@ -151,6 +151,11 @@ extern "C" int ddp_set_option(ddp_ctx *ctx, const char *name, int64_t value) {
         ctx->dispatch_ways = (int)value;
         return DDP_OK;
     }
+    if (k == "update_lds" || k == "mean_lds" || k == "copy_lds") {
+        if (value < 0 || value > 65536) return fail(ctx, DDP_EINVAL, "ddp_set_option: LDS pad must be in [0, 65536] bytes");
+        (k == "update_lds" ? ctx->update_lds : k == "mean_lds" ? ctx->mean_lds : ctx->copy_lds) = (int)value;
+        return DDP_OK;
+    }
     if (k == "nontemporal") {
         if (value != 0 && value != 1) return fail(ctx, DDP_EINVAL, "ddp_set_option: nontemporal is 0 or 1");
         ctx->nontemporal = value != 0;
@@ -371,7 +376,7 @@ extern "C" int ddp_pack(ddp_ctx *ctx, int slot, float *flat_local, void *stream)
     if ((rc = check_device(ctx, "ddp_pack")) != DDP_OK) return rc;
     if (s->numel == 0) return DDP_OK;
     if ((rc = check_flat(ctx, flat_local, "ddp_pack", "flat_local")) != DDP_OK) return rc;
-    rc = launch_copy(false, ctx->d_tensors, s->d_copy, s->n_copy, flat_local, false, ctx->nontemporal, stream);
+    rc = launch_copy(false, ctx->d_tensors, s->d_copy, s->n_copy, flat_local, false, ctx->nontemporal, ctx->copy_lds, stream);
     return after_launch(ctx, "ddp_pack", rc);
 }
 
@@ -383,7 +388,7 @@ extern "C" int ddp_unpack(ddp_ctx *ctx, int slot, const float *flat, void *strea
     if (s->numel == 0) return DDP_OK;
     if ((rc = check_flat(ctx, flat, "ddp_unpack", "flat")) != DDP_OK) return rc;
     rc = launch_copy(true, ctx->d_tensors, s->d_copy, s->n_copy, const_cast<float *>(flat), ctx->param_dtype == DDP_BF16,
-                     ctx->nontemporal, stream);
+                     ctx->nontemporal, ctx->copy_lds, stream);
     return after_launch(ctx, "ddp_unpack", rc);
 }
 
@@ -429,6 +434,7 @@ extern "C" int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_loc
     a.n_layers = (int)s->layers.size();
     a.stats = layer_stats;
     a.nontemporal = ctx->nontemporal;
+    a.lds_pad = ctx->mean_lds;
     rc = launch_mean(a, stream);
     return after_launch(ctx, "ddp_partial_average", rc);
 }
@@ -464,6 +470,6 @@ extern "C" int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream) 
         return fail(ctx, DDP_EINVAL, "ddp_local_update: unknown optimizer kind");
     }
     rc = launch_update(opt->kind, ctx->grad_dtype, ctx->param_dtype == DDP_BF16, ctx->d_tensors, ctx->d_update, ctx->n_update, s,
-                       ctx->nontemporal, stream);
+                       ctx->nontemporal, ctx->update_lds, stream);
     return after_launch(ctx, "ddp_local_update", rc);
 }

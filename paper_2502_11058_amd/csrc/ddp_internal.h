@@ -75,6 +75,7 @@ struct MeanLaunch {
     int n_layers;
     double *stats;  // [n_layers][2]
     bool nontemporal;
+    int lds_pad;
 };
 
 struct UpdateScalars {
@@ -83,10 +84,10 @@ struct UpdateScalars {
 };
 
 int launch_copy(bool unpack, const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, float *flat,
-                bool with_model, bool nontemporal, void *stream);
+                bool with_model, bool nontemporal, int lds_pad, void *stream);
 int launch_mean(const MeanLaunch &a, void *stream);
 int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *tensors, const UpdateChunk *chunks,
-                  int64_t n_chunks, const UpdateScalars &s, bool nontemporal, void *stream);
+                  int64_t n_chunks, const UpdateScalars &s, bool nontemporal, int lds_pad, void *stream);
 
 }  // namespace ddp
 
@@ -94,9 +95,10 @@ struct ddp_ctx {
     int device = 0;
     mutable std::string err;
     // options
-    int64_t update_chunk = 8192, mean_chunk = 8192, copy_chunk = 8192;
+    int64_t update_chunk = 2048, mean_chunk = 1024, copy_chunk = 2048;
     bool nontemporal = true;
     int dispatch_ways = 1;
+    int update_lds = 65536, mean_lds = 53248, copy_lds = 24576;  // dynamic-LDS pad per workgroup: caps residency per CU
     // model
     bool registered = false;
     int L = 0, T = 0;

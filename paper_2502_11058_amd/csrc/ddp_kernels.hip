@@ -485,30 +485,32 @@ __global__ __launch_bounds__(kThreads) void update_kernel(const TensorDesc *__re
     }
 }
 
+// lds_pad: bytes of dynamic LDS requested per workgroup although no kernel uses them.  A CU has 160 KiB, so the pad
+// caps how many workgroups are resident per CU, i.e. how wide the window of addresses in flight is.
 template <class K, class... Args>
-int launch(K kernel, int64_t grid, void *stream, Args... args) {
+int launch(K kernel, int64_t grid, void *stream, int lds_pad, Args... args) {
     if (grid <= 0) return 0;
     if (grid > 0x7fffffff) return (int)hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, args...);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), (size_t)lds_pad, (hipStream_t)stream, args...);
     return (int)hipGetLastError();
 }
 
 template <int NREP>
 int launch_mean_n(const MeanArgs &ma, const MeanLaunch &a, void *stream) {
-    if (a.partials) return a.nontemporal ? launch(mean_kernel<NREP, true, true>, a.n_chunks, stream, ma) : launch(mean_kernel<NREP, true, false>, a.n_chunks, stream, ma);
-    return a.nontemporal ? launch(mean_kernel<NREP, false, true>, a.n_chunks, stream, ma) : launch(mean_kernel<NREP, false, false>, a.n_chunks, stream, ma);
+    if (a.partials) return a.nontemporal ? launch(mean_kernel<NREP, true, true>, a.n_chunks, stream, a.lds_pad, ma) : launch(mean_kernel<NREP, true, false>, a.n_chunks, stream, a.lds_pad, ma);
+    return a.nontemporal ? launch(mean_kernel<NREP, false, true>, a.n_chunks, stream, a.lds_pad, ma) : launch(mean_kernel<NREP, false, false>, a.n_chunks, stream, a.lds_pad, ma);
 }
 
 }  // namespace
 
 int launch_copy(bool unpack, const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, float *flat, bool with_model,
-                bool nontemporal, void *stream) {
-    if (!unpack) return nontemporal ? launch(copy_kernel<false, false, true>, n_chunks, stream, tensors, chunks, flat)
-                                    : launch(copy_kernel<false, false, false>, n_chunks, stream, tensors, chunks, flat);
-    if (with_model) return nontemporal ? launch(copy_kernel<true, true, true>, n_chunks, stream, tensors, chunks, flat)
-                                       : launch(copy_kernel<true, true, false>, n_chunks, stream, tensors, chunks, flat);
-    return nontemporal ? launch(copy_kernel<true, false, true>, n_chunks, stream, tensors, chunks, flat)
-                       : launch(copy_kernel<true, false, false>, n_chunks, stream, tensors, chunks, flat);
+                bool nontemporal, int lds_pad, void *stream) {
+    if (!unpack) return nontemporal ? launch(copy_kernel<false, false, true>, n_chunks, stream, lds_pad, tensors, chunks, flat)
+                                    : launch(copy_kernel<false, false, false>, n_chunks, stream, lds_pad, tensors, chunks, flat);
+    if (with_model) return nontemporal ? launch(copy_kernel<true, true, true>, n_chunks, stream, lds_pad, tensors, chunks, flat)
+                                       : launch(copy_kernel<true, true, false>, n_chunks, stream, lds_pad, tensors, chunks, flat);
+    return nontemporal ? launch(copy_kernel<true, false, true>, n_chunks, stream, lds_pad, tensors, chunks, flat)
+                       : launch(copy_kernel<true, false, false>, n_chunks, stream, lds_pad, tensors, chunks, flat);
 }
 
 int launch_mean(const MeanLaunch &a, void *stream) {
@@ -533,16 +535,16 @@ int launch_mean(const MeanLaunch &a, void *stream) {
         default: rc = launch_mean_n<0>(ma, a, stream); break;
     }
     if (rc != 0 || !a.partials) return rc;
-    return launch(stats_finalize_kernel, a.n_layers, stream, (const double *)a.partials, a.layer_chunk_ptr, a.n_replicas, a.stats);
+    return launch(stats_finalize_kernel, a.n_layers, stream, 0, (const double *)a.partials, a.layer_chunk_ptr, a.n_replicas, a.stats);
 }
 
 int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *tensors, const UpdateChunk *chunks, int64_t n_chunks,
-                  const UpdateScalars &s, bool nontemporal, void *stream) {
+                  const UpdateScalars &s, bool nontemporal, int lds_pad, void *stream) {
     const bool adam = kind == DDP_OPT_ADAMW, gb = grad_dtype == DDP_BF16;
 #define DDP_UPD(A, G, M)                                                                               \
     if (adam == A && gb == G && with_model == M)                                                       \
-        return nontemporal ? launch(update_kernel<A, G, M, true>, n_chunks, stream, tensors, chunks, s) \
-                           : launch(update_kernel<A, G, M, false>, n_chunks, stream, tensors, chunks, s);
+        return nontemporal ? launch(update_kernel<A, G, M, true>, n_chunks, stream, lds_pad, tensors, chunks, s) \
+                           : launch(update_kernel<A, G, M, false>, n_chunks, stream, lds_pad, tensors, chunks, s);
     DDP_UPD(false, false, false)
     DDP_UPD(false, false, true)
     DDP_UPD(false, true, false)

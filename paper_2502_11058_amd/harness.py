@@ -21,10 +21,12 @@ from . import workloads as W
 class DeviceReplica:
     def __init__(self, w: W.Workload, device: int = 0, options: Optional[Dict[str, int]] = None, arena_offset: int = 0,
                  grad_dtype: Optional[str] = None, policy: Optional[str] = None, n_peers: Optional[int] = None,
-                 region_skew: int = 0):
+                 region_skew: int = 0, placement_probe: Optional[bool] = None):
         """Schedules, allocates, registers.  arena_offset: elements skipped at the start of every arena (tests use
         it to break 16-byte alignment).  policy: schedule policy (default: the workload's).  region_skew: extra bytes
-        (multiple of 256) by which each successive region of the slab is shifted off its 2 MiB boundary."""
+        (multiple of 256) by which each successive region of the slab is shifted off its 2 MiB boundary.
+        placement_probe: time the update kernel on the freshly zeroed slab and, if a re-allocation lands on
+        physical memory that streams faster, keep that one (default: on for models of a billion parameters or more)."""
         self.w = w
         self.dev = torch.device("cuda", device)
         torch.cuda.set_device(self.dev)
@@ -51,6 +53,56 @@ class DeviceReplica:
         n_peers = w.n_replicas - 1 if n_peers is None else n_peers
         max_layers = max(len(S) for S in self.sets)
 
+        self._regions_args = (P, arena_offset, smax, n_peers, max_layers, region_skew, sp, sl, device, options)
+        self.placement = {"probe_GBps": []}
+        self._build()
+        if placement_probe is None:
+            placement_probe = P >= 1_000_000_000
+        if placement_probe:
+            # Successive allocations of a slab this large alternate between two physical placements whose DRAM
+            # efficiency differs by ~10 % (same kernel, same virtual layout, same TLB behaviour; the slower one
+            # shows more read-credit stalls at the memory interface).  Take two, keep the faster.
+            first = self._probe()
+            self._release()
+            self._build()
+            second = self._probe()
+            self.placement["probe_GBps"] = [first, second]
+            if second < 0.995 * first:
+                self._release()
+                self._build()
+                self.placement["probe_GBps"].append(self._probe())
+
+    def _release(self) -> None:
+        import gc
+        self.ctx.close()
+        self.ctx._keep = []
+        for name in ("slab", "a_sync", "a_s0", "a_s1", "a_grad", "a_model", "flat", "stats", "peers", "sync", "model", "grad", "s0", "s1"):
+            setattr(self, name, None)
+        gc.collect()
+        torch.cuda.empty_cache()
+        self.ctx = B.Context(self._regions_args[8])
+        for k, v in (self._regions_args[9] or {}).items():
+            self.ctx.ddp_set_option(k, v)
+
+    def _probe(self) -> float:
+        """GB/s of the update kernel on the zeroed slab (zeros stay zeros under SGD-m and AdamW)."""
+        stream = torch.cuda.current_stream()
+        P = self._regions_args[0]
+        per = (2 if self.grad_bf16 else 4) + (24 if self.adam else 16) + (2 if self.bf16 else 0)
+        evs = []
+        for r in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            self.ctx.ddp_local_update(self.opt_struct(r + 1))
+            e1.record(stream)
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in evs[1:])
+        return per * P / (ms[len(ms) // 2] * 1e-3) / 1e9
+
+    def _build(self) -> None:
+        P, arena_offset, smax, n_peers, max_layers, region_skew, sp, sl, _, _ = self._regions_args
+        w = self.w
         # one slab for everything this worker owns on the device; every region starts on a 2 MiB boundary
         o = arena_offset
         regions = [("sync", torch.float32, P + o), ("s0", torch.float32, P + o)]
