@@ -188,6 +188,23 @@ def main() -> int:
                 "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
                 "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"], "avg_launch_ms": kernels[dom]["avg_ms"]}
 
+    # ---- pass 3: the fused entry point (both cases of Eq. (5) in one pass), K steps, wall clock --------------------
+    r2 = r1 + args.steps
+    for r in range(r2, r2 + H):
+        rep.fused_step(r, with_stats=with_stats)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for r in range(r2 + H, r2 + H + args.steps):
+        rep.fused_step(r, with_stats=with_stats)
+    torch.cuda.synchronize()
+    wall_f = time.perf_counter() - t0
+    upd_per_param = algorithmic_bytes(w, 0)["local_update"] / w.n_params
+    fused_bytes = float(sum(4 * (w.n_replicas - 1) * rep.slot_numel[r % H] + upd_per_param * w.n_params
+                            for r in range(r2 + H, r2 + H + args.steps)))
+    fused = {"entry_point": "ddp_fused_sync_update", "ms_per_step": 1e3 * wall_f / args.steps,
+             "value_vs_4call_bytes": total_bytes / wall_f / 1e9, "own_alg_bytes_per_step_avg": fused_bytes / args.steps,
+             "GB/s_on_own_bytes": fused_bytes / wall_f / 1e9, "params_per_s": w.n_params * args.steps / wall_f}
+
     out = {
         "metric": "partial-sync+update step: achieved HBM GB/s & % of peak; params/s",
         "value": gbs, "unit": "GB/s", "pct_of_peak": 100.0 * gbs / HBM_PEAK_GBS,
@@ -198,7 +215,7 @@ def main() -> int:
                                f"{w.optimizer}, schedule {args.policy or w.policy}, slot sizes {rep.slot_numel}",
                    "alg_bytes_per_step_avg": total_bytes / args.steps, "layer_stats": with_stats, "options": options,
                    "placement_probe_GBps": [round(x, 1) for x in rep.placement["probe_GBps"]]},
-        "kernels": kernels, "roofline": roofline,
+        "kernels": kernels, "roofline": roofline, "fused": fused,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(rep, w)

@@ -24,7 +24,7 @@ STATUS = {0: "DDP_OK", 1: "DDP_EINVAL", 2: "DDP_ESHAPE", 3: "DDP_EALIGN", 4: "DD
 EXPORTS = [
     "ddp_schedule", "ddp_schedule_cost", "ddp_schedule_alg2_solutions", "ddp_schedule_fill_bubbles", "ddp_schedule_time_model", "ddp_create", "ddp_destroy", "ddp_set_option",
     "ddp_register_model", "ddp_set_schedule", "ddp_slot_numel", "ddp_slot_num_layers", "ddp_slot_num_tensors",
-    "ddp_slot_layout", "ddp_pack", "ddp_partial_average", "ddp_unpack", "ddp_local_update", "ddp_last_error",
+    "ddp_slot_layout", "ddp_pack", "ddp_partial_average", "ddp_unpack", "ddp_local_update", "ddp_fused_sync_update", "ddp_last_error",
 ]
 
 
@@ -68,6 +68,7 @@ def lib():
         l.ddp_unpack.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         l.ddp_partial_average.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         l.ddp_local_update.argtypes = [C.c_void_p, C.POINTER(ddp_opt), C.c_void_p]
+        l.ddp_fused_sync_update.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.POINTER(ddp_opt), C.c_void_p]
         l.ddp_schedule.argtypes = [C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7
         l.ddp_schedule_cost.argtypes = [C.c_int, C.c_int] + [C.c_void_p] * 5
         l.ddp_schedule_alg2_solutions.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -268,6 +269,12 @@ class Context:
 
     def ddp_local_update(self, opt: ddp_opt, stream=None) -> None:
         _check(lib().ddp_local_update(self._h, C.byref(opt), _stream_handle(stream)), self._h)
+
+    def ddp_fused_sync_update(self, slot: int, peers, N: int, local_rank: int, layer_stats, opt: ddp_opt, stream=None) -> None:
+        arr = _dev_ptrs(list(peers)) if peers else None
+        _check(lib().ddp_fused_sync_update(self._h, slot, None if arr is None else C.addressof(arr), N, local_rank,
+                                           None if layer_stats is None else layer_stats.data_ptr(), C.byref(opt),
+                                           _stream_handle(stream)), self._h)
 
     def last_error(self) -> str:
         return lib().ddp_last_error(self._h).decode()

@@ -43,10 +43,14 @@ static int upload(const ddp_ctx *ctx, const std::vector<T> &host, T **dev) {
 static void free_slot(SlotTables &s) {
     if (s.d_copy) (void)hipFree(s.d_copy);
     if (s.d_mean) (void)hipFree(s.d_mean);
-    if (s.d_layer_chunk_ptr) (void)hipFree(s.d_layer_chunk_ptr);
+    if (s.d_layer_ranges) (void)hipFree(s.d_layer_ranges);
+    if (s.d_tensor_flat_off) (void)hipFree(s.d_tensor_flat_off);
+    if (s.d_fused_ranges) (void)hipFree(s.d_fused_ranges);
     s.d_copy = nullptr;
     s.d_mean = nullptr;
-    s.d_layer_chunk_ptr = nullptr;
+    s.d_layer_ranges = nullptr;
+    s.d_tensor_flat_off = nullptr;
+    s.d_fused_ranges = nullptr;
 }
 
 static void drop_schedule(ddp_ctx *c) {
@@ -62,6 +66,8 @@ static void drop_model(ddp_ctx *c) {
     drop_schedule(c);
     if (c->d_tensors) (void)hipFree(c->d_tensors);
     if (c->d_update) (void)hipFree(c->d_update);
+    if (c->d_tensor_chunk_base) (void)hipFree(c->d_tensor_chunk_base);
+    c->d_tensor_chunk_base = nullptr;
     c->d_tensors = nullptr;
     c->d_update = nullptr;
     c->n_update = 0;
@@ -218,14 +224,20 @@ extern "C" int ddp_register_model(ddp_ctx *ctx, int L, int T, const int32_t *lay
 
     // update table: every tensor cut into runs of update_chunk elements
     std::vector<UpdateChunk> uc;
-    for (int t = 0; t < T; ++t)
+    ctx->tensor_chunk_base.assign((size_t)T + 1, 0);
+    for (int t = 0; t < T; ++t) {
+        ctx->tensor_chunk_base[(size_t)t] = (int32_t)uc.size();
         for (int64_t b = 0; b < numel[t]; b += ctx->update_chunk) {
             int64_t n = std::min<int64_t>(ctx->update_chunk, numel[t] - b);
             uc.push_back({b, t, (int32_t)n});
         }
+    }
+    ctx->tensor_chunk_base[(size_t)T] = (int32_t)uc.size();
+    ctx->n_update = (int64_t)uc.size();
     interleave_segments(uc, ctx->dispatch_ways);
     rc = upload(ctx, ts, &ctx->d_tensors);
     if (rc == DDP_OK) rc = upload(ctx, uc, &ctx->d_update);
+    if (rc == DDP_OK) rc = upload(ctx, ctx->tensor_chunk_base, &ctx->d_tensor_chunk_base);
     if (rc != DDP_OK) {
         drop_model(ctx);
         return rc;
@@ -260,17 +272,21 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
         SlotTables &st = slots[(size_t)s];
         std::vector<CopyChunk> cc;
         std::vector<MeanChunk> mc;
-        std::vector<int32_t> lcp;
+        std::vector<int32_t> lcp, fused_ranges;
+        std::vector<int64_t> tflat((size_t)ctx->T, -1);
         int64_t off = 0;
         for (int j = set_ptr[s]; j < set_ptr[s + 1]; ++j) {
             const int l = set_layers[j];
             st.layers.push_back(l);
             st.layer_begin.push_back(off);
             lcp.push_back((int32_t)mc.size());
+            fused_ranges.push_back(ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)l]]);
+            fused_ranges.push_back(ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)l + 1]]);
             const int64_t layer_start = off;
             for (int t = ctx->layer_first_tensor[(size_t)l]; t < ctx->layer_first_tensor[(size_t)l + 1]; ++t) {
                 st.tensors.push_back(t);
                 st.tensor_off.push_back(off);
+                tflat[(size_t)t] = off;
                 for (int64_t b = 0; b < ctx->numel[(size_t)t]; b += ctx->copy_chunk) {
                     int64_t n = std::min<int64_t>(ctx->copy_chunk, ctx->numel[(size_t)t] - b);
                     cc.push_back({b, off + b, t, (int32_t)n});
@@ -296,12 +312,20 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
         interleave_segments(mc, ctx->dispatch_ways);
         rc = upload(ctx, cc, &st.d_copy);
         if (rc == DDP_OK) rc = upload(ctx, mc, &st.d_mean);
-        if (rc == DDP_OK) rc = upload(ctx, lcp, &st.d_layer_chunk_ptr);
+        std::vector<int32_t> mean_ranges;
+        for (size_t i = 0; i + 1 < lcp.size(); ++i) {
+            mean_ranges.push_back(lcp[i]);
+            mean_ranges.push_back(lcp[i + 1]);
+        }
+        if (rc == DDP_OK) rc = upload(ctx, mean_ranges, &st.d_layer_ranges);
+        if (rc == DDP_OK) rc = upload(ctx, tflat, &st.d_tensor_flat_off);
+        if (rc == DDP_OK) rc = upload(ctx, fused_ranges, &st.d_fused_ranges);
         if (rc != DDP_OK) {
             for (auto &x : slots) free_slot(x);
             return rc;
         }
     }
+    max_mean_chunks = std::max(max_mean_chunks, ctx->n_update);  // the fused step keeps one partial per update chunk
     if (max_mean_chunks > 0) {
         hipError_t e = hipMalloc((void **)&ctx->d_partials, (size_t)max_mean_chunks * 2 * sizeof(double));
         if (e != hipSuccess) {
@@ -430,7 +454,7 @@ extern "C" int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_loc
     a.chunks = s->d_mean;
     a.n_chunks = s->n_mean;
     a.partials = layer_stats ? ctx->d_partials : nullptr;
-    a.layer_chunk_ptr = s->d_layer_chunk_ptr;
+    a.layer_ranges = s->d_layer_ranges;
     a.n_layers = (int)s->layers.size();
     a.stats = layer_stats;
     a.nontemporal = ctx->nontemporal;
@@ -439,37 +463,82 @@ extern "C" int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_loc
     return after_launch(ctx, "ddp_partial_average", rc);
 }
 
-extern "C" int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream) {
-    if (!ctx) return fail(nullptr, DDP_EINVAL, "ddp_local_update: ctx is NULL");
-    if (!ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_local_update: no model registered");
-    if (!opt) return fail(ctx, DDP_EINVAL, "ddp_local_update: opt is NULL");
-    int rc = check_device(ctx, "ddp_local_update");
-    if (rc != DDP_OK) return rc;
-    UpdateScalars s{};
+static int make_scalars(ddp_ctx *ctx, const char *who, const ddp_opt *opt, UpdateScalars &s) {
+    if (!opt) return fail(ctx, DDP_EINVAL, std::string(who) + ": opt is NULL");
     if (opt->kind == DDP_OPT_SGDM) {
         s.lr = opt->lr;
         s.mu = opt->momentum;
-    } else if (opt->kind == DDP_OPT_ADAMW) {
-        if (!ctx->has_state1) return fail(ctx, DDP_ESTATE, "ddp_local_update: AdamW needs state1_ptr for every tensor");
-        if (opt->step < 1) return fail(ctx, DDP_EINVAL, "ddp_local_update: step is 1-based");
-        if (!(opt->beta1 >= 0.0f && opt->beta1 < 1.0f && opt->beta2 >= 0.0f && opt->beta2 < 1.0f))
-            return fail(ctx, DDP_EINVAL, "ddp_local_update: betas must be in [0, 1)");
-        // bias corrections in fp64, handed to the kernel as fp32 factors
-        const double bc1 = 1.0 - std::pow((double)opt->beta1, (double)opt->step);
-        const double bc2 = 1.0 - std::pow((double)opt->beta2, (double)opt->step);
-        const float inv_bc1 = (float)(1.0 / bc1);
-        s.beta1 = opt->beta1;
-        s.beta2 = opt->beta2;
-        s.omb1 = 1.0f - opt->beta1;
-        s.omb2 = 1.0f - opt->beta2;
-        s.decay = 1.0f - opt->lr * opt->weight_decay;
-        s.step_size = opt->lr * inv_bc1;
-        s.rsqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
-        s.eps = opt->eps;
-    } else {
-        return fail(ctx, DDP_EINVAL, "ddp_local_update: unknown optimizer kind");
+        return DDP_OK;
     }
+    if (opt->kind != DDP_OPT_ADAMW) return fail(ctx, DDP_EINVAL, std::string(who) + ": unknown optimizer kind");
+    if (!ctx->has_state1) return fail(ctx, DDP_ESTATE, std::string(who) + ": AdamW needs state1_ptr for every tensor");
+    if (opt->step < 1) return fail(ctx, DDP_EINVAL, std::string(who) + ": step is 1-based");
+    if (!(opt->beta1 >= 0.0f && opt->beta1 < 1.0f && opt->beta2 >= 0.0f && opt->beta2 < 1.0f))
+        return fail(ctx, DDP_EINVAL, std::string(who) + ": betas must be in [0, 1)");
+    // bias corrections in fp64, handed to the kernel as fp32 factors
+    const double bc1 = 1.0 - std::pow((double)opt->beta1, (double)opt->step);
+    const double bc2 = 1.0 - std::pow((double)opt->beta2, (double)opt->step);
+    const float inv_bc1 = (float)(1.0 / bc1);
+    s.beta1 = opt->beta1;
+    s.beta2 = opt->beta2;
+    s.omb1 = 1.0f - opt->beta1;
+    s.omb2 = 1.0f - opt->beta2;
+    s.decay = 1.0f - opt->lr * opt->weight_decay;
+    s.step_size = opt->lr * inv_bc1;
+    s.rsqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
+    s.eps = opt->eps;
+    return DDP_OK;
+}
+
+extern "C" int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream) {
+    if (!ctx) return fail(nullptr, DDP_EINVAL, "ddp_local_update: ctx is NULL");
+    if (!ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_local_update: no model registered");
+    UpdateScalars s{};
+    int rc = make_scalars(ctx, "ddp_local_update", opt, s);
+    if (rc != DDP_OK) return rc;
+    if ((rc = check_device(ctx, "ddp_local_update")) != DDP_OK) return rc;
     rc = launch_update(opt->kind, ctx->grad_dtype, ctx->param_dtype == DDP_BF16, ctx->d_tensors, ctx->d_update, ctx->n_update, s,
                        ctx->nontemporal, ctx->update_lds, stream);
     return after_launch(ctx, "ddp_local_update", rc);
+}
+
+extern "C" int ddp_fused_sync_update(ddp_ctx *ctx, int slot, const float *const *peers, int N, int local_rank, double *layer_stats,
+                                     const ddp_opt *opt, void *stream) {
+    int rc;
+    const SlotTables *st = slot_of(ctx, slot, "ddp_fused_sync_update", &rc);
+    if (!st) return rc;
+    UpdateScalars s{};
+    if ((rc = make_scalars(ctx, "ddp_fused_sync_update", opt, s)) != DDP_OK) return rc;
+    if ((rc = check_device(ctx, "ddp_fused_sync_update")) != DDP_OK) return rc;
+    if (N < 1 || N > DDP_MAX_REPLICAS) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update: N must be in [1, " + std::to_string((int)DDP_MAX_REPLICAS) + "]");
+    if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update: local_rank out of range");
+    if (N > 1 && !peers) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update: peers is NULL");
+    if (layer_stats && !aligned(layer_stats, 8)) return fail(ctx, DDP_EALIGN, "ddp_fused_sync_update: layer_stats must be 8-byte aligned");
+    FusedLaunch f{};
+    int p = 0;
+    for (int k = 0; k < N; ++k) {
+        if (k == local_rank) continue;
+        const float *q = peers[p++];
+        if (st->numel > 0 && (rc = check_flat(ctx, q, "ddp_fused_sync_update", "a peer buffer")) != DDP_OK) return rc;
+        f.x[k] = q;
+    }
+    f.n_replicas = N;
+    f.local_rank = local_rank;
+    f.inv_n = 1.0f / (float)N;
+    f.kind = opt->kind;
+    f.grad_dtype = ctx->grad_dtype;
+    f.with_model = ctx->param_dtype == DDP_BF16;
+    f.tensors = ctx->d_tensors;
+    f.chunks = ctx->d_update;
+    f.n_chunks = ctx->n_update;
+    f.tensor_flat_off = st->d_tensor_flat_off;
+    f.tensor_chunk_base = ctx->d_tensor_chunk_base;
+    f.chunk_elems = (int)ctx->update_chunk;
+    f.s = s;
+    f.partials = (layer_stats && !st->layers.empty()) ? ctx->d_partials : nullptr;
+    f.layer_ranges = st->d_fused_ranges;
+    f.n_layers = (int)st->layers.size();
+    f.stats = layer_stats;
+    f.lds_pad = ctx->update_lds;
+    return after_launch(ctx, "ddp_fused_sync_update", launch_fused(f, stream));
 }

@@ -59,7 +59,9 @@ struct SlotTables {
     int64_t n_copy = 0;
     MeanChunk *d_mean = nullptr;
     int64_t n_mean = 0;
-    int32_t *d_layer_chunk_ptr = nullptr;  // n_layers + 1: first mean chunk of each layer
+    int32_t *d_layer_ranges = nullptr;     // per layer of the slot: [first, last) mean chunk
+    int64_t *d_tensor_flat_off = nullptr;  // per registered tensor: first flat index in this slot, -1 if unscheduled
+    int32_t *d_fused_ranges = nullptr;     // per layer of the slot: [first, last) update chunk (registration order)
 };
 
 // ---- launchers (ddp_kernels.hip) -------------------------------------------------------------------------------
@@ -71,7 +73,7 @@ struct MeanLaunch {
     const MeanChunk *chunks;
     int64_t n_chunks;
     double *partials;  // [n_chunks][2] or nullptr when no statistics are wanted
-    const int32_t *layer_chunk_ptr;
+    const int32_t *layer_ranges;  // per layer [first, last) partial index
     int n_layers;
     double *stats;  // [n_layers][2]
     bool nontemporal;
@@ -86,6 +88,26 @@ struct UpdateScalars {
 int launch_copy(bool unpack, const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, float *flat,
                 bool with_model, bool nontemporal, int lds_pad, void *stream);
 int launch_mean(const MeanLaunch &a, void *stream);
+struct FusedLaunch {
+    const float *x[DDP_MAX_REPLICAS];  // peers in rank order (entry local_rank unused)
+    int n_replicas, local_rank;
+    float inv_n;
+    int kind, grad_dtype;
+    bool with_model;
+    const TensorDesc *tensors;
+    const UpdateChunk *chunks;
+    int64_t n_chunks;
+    const int64_t *tensor_flat_off;
+    const int32_t *tensor_chunk_base;
+    int chunk_elems;
+    UpdateScalars s;
+    double *partials;  // nullptr: no statistics
+    const int32_t *layer_ranges;
+    int n_layers;
+    double *stats;
+    int lds_pad;
+};
+int launch_fused(const FusedLaunch &f, void *stream);
 int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *tensors, const UpdateChunk *chunks,
                   int64_t n_chunks, const UpdateScalars &s, bool nontemporal, int lds_pad, void *stream);
 
@@ -111,6 +133,8 @@ struct ddp_ctx {
     ddp::TensorDesc *d_tensors = nullptr;
     ddp::UpdateChunk *d_update = nullptr;
     int64_t n_update = 0;
+    std::vector<int32_t> tensor_chunk_base;  // T + 1: first update chunk of each tensor, registration order
+    int32_t *d_tensor_chunk_base = nullptr;
     // schedule
     int H = 0;
     std::vector<ddp::SlotTables> slots;

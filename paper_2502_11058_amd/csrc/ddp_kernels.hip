@@ -313,13 +313,14 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
 }
 
 // Per layer: add the chunk partials of that layer in a fixed order (thread-strided, then the workgroup tree) and
-// scale the divergence by 1/N (Sec. 3.4: Gamma = 1/K sum_k ||wbar - w^k||^2, here per layer).
+// scale the divergence by 1/N (Sec. 3.4: Gamma = 1/K sum_k ||wbar - w^k||^2, here per layer).  Layer l owns the
+// partials [ranges[2l], ranges[2l+1]).
 __global__ __launch_bounds__(kThreads) void stats_finalize_kernel(const double *__restrict__ partials,
-                                                                  const int32_t *__restrict__ layer_chunk_ptr, int n_replicas,
+                                                                  const int32_t *__restrict__ ranges, int n_replicas,
                                                                   double *__restrict__ stats) {
     __shared__ double lds[2][kThreads / kWave];
     const int l = blockIdx.x;
-    const int c0 = layer_chunk_ptr[l], c1 = layer_chunk_ptr[l + 1];
+    const int c0 = ranges[2 * l], c1 = ranges[2 * l + 1];
     double g = 0.0, m = 0.0;
     for (int c = c0 + (int)threadIdx.x; c < c1; c += kThreads) {
         g += partials[2 * (int64_t)c];
@@ -389,13 +390,10 @@ struct GradVec<true> {
 // Eq. (5), first case, fused: one pass reads gradient, parameter and optimizer state and writes parameter,
 // state and (if present) the bf16 model copy.  ADAM selects AdamW, else SGD with momentum.
 template <bool ADAM, bool GBF16, bool MODEL, bool NT>
-__global__ __launch_bounds__(kThreads) void update_kernel(const TensorDesc *__restrict__ tensors, const UpdateChunk *__restrict__ chunks,
-                                                          const UpdateScalars s) {
+__device__ __forceinline__ void update_chunk_body(const TensorDesc &td, const UpdateChunk &ch, const UpdateScalars &s) {
     typedef GradVec<GBF16> G;
     typedef typename G::elem gelem;
     typedef typename G::vec gvec;
-    const UpdateChunk ch = chunks[blockIdx.x];
-    const TensorDesc td = tensors[ch.tensor];
     float *p = td.sync + ch.begin;
     float *s0 = td.state0 + ch.begin;
     float *s1 = ADAM ? td.state1 + ch.begin : s0;  // unused without ADAM
@@ -485,6 +483,191 @@ __global__ __launch_bounds__(kThreads) void update_kernel(const TensorDesc *__re
     }
 }
 
+template <bool ADAM, bool GBF16, bool MODEL, bool NT>
+__global__ __launch_bounds__(kThreads) void update_kernel(const TensorDesc *__restrict__ tensors, const UpdateChunk *__restrict__ chunks,
+                                                          const UpdateScalars s) {
+    const UpdateChunk ch = chunks[blockIdx.x];
+    const TensorDesc td = tensors[ch.tensor];
+    update_chunk_body<ADAM, GBF16, MODEL, NT>(td, ch, s);
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// fused synchronisation + update
+// ---------------------------------------------------------------------------------------------------------------
+
+struct FusedArgs {
+    const float *x[DDP_MAX_REPLICAS];  // peers' flat buffers in rank order; entry local_rank is unused
+    const TensorDesc *tensors;
+    const UpdateChunk *chunks;
+    const int64_t *tensor_flat_off;     // per tensor: first flat index in this slot, or -1 if not scheduled
+    const int32_t *tensor_chunk_base;   // per tensor: index of its first chunk in registration order
+    double *partials;                   // [n_chunks][2], only touched for scheduled chunks
+    UpdateScalars s;
+    float inv_n;
+    int n;
+    int local_rank;
+    int chunk_elems;
+};
+
+// Both cases of Eq. (5) in one pass.  For a chunk of a scheduled tensor the parameter is first replaced by the
+// average over the N replicas (local values straight from the tensor, peers from their flat buffers at the
+// tensor's flat offset; same rank-ordered fp32 sum and 1/N multiply as mean_kernel), then updated; every other
+// chunk is updated only.  Result: the bits that pack -> partial average -> unpack -> local update produce, without
+// the flat round trips.  NREP > 0: replica count known at compile time; 0: run-time loop.
+template <bool ADAM, bool GBF16, bool MODEL, int NREP, bool STATS>
+__global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
+    typedef GradVec<GBF16> G;
+    typedef typename G::elem gelem;
+    typedef typename G::vec gvec;
+    constexpr bool NT = true;
+    __shared__ double lds[2][kThreads / kWave];
+    const UpdateChunk ch = a.chunks[blockIdx.x];
+    const TensorDesc td = a.tensors[ch.tensor];
+    const int64_t toff = a.tensor_flat_off[ch.tensor];
+    if (toff < 0) {  // uniform for the workgroup
+        update_chunk_body<ADAM, GBF16, MODEL, NT>(td, ch, a.s);
+        return;
+    }
+    const UpdateScalars &s = a.s;
+    const int64_t fo = toff + ch.begin;
+    float *p = td.sync + ch.begin;
+    float *s0 = td.state0 + ch.begin;
+    float *s1 = ADAM ? td.state1 + ch.begin : s0;
+    const gelem *g = reinterpret_cast<const gelem *>(td.grad) + ch.begin;
+    unsigned short *mdl = MODEL ? td.model + ch.begin : reinterpret_cast<unsigned short *>(p);
+    const int n = ch.count;
+    const int tid = threadIdx.x;
+    const int nrep = NREP > 0 ? NREP : a.n;
+    const int lr = a.local_rank;
+    const float inv_n = a.inv_n;
+    double gsum = 0.0, msum = 0.0;
+
+    // replica k's values for this chunk: the tensor itself for the local rank, else the peer's flat buffer
+    auto src = [&](int k) -> const float * { return k == lr ? p : a.x[k] + fo; };
+
+    auto one = [&](int i) {
+        float acc = src(0)[i];
+        for (int k = 1; k < nrep; ++k) acc = acc + src(k)[i];
+        const float m = acc * inv_n;
+        if constexpr (STATS) {
+            for (int k = 0; k < nrep; ++k) {
+                const float d = m - src(k)[i];
+                gsum += (double)d * (double)d;
+            }
+            msum += (double)m * (double)m;
+        }
+        float pi = m, av = s0[i];
+        const float gi = G::widen1(g[i]);
+        if constexpr (ADAM) {
+            float bv = s1[i];
+            adamw_one(gi, pi, av, bv, s);
+            s1[i] = bv;
+        } else {
+            sgdm_one(gi, pi, av, s);
+        }
+        p[i] = pi;
+        s0[i] = av;
+        if constexpr (MODEL) mdl[i] = bf16_rne(pi);
+    };
+
+    const int h = head_to_16B(p, n);
+    bool vec_ok = (reinterpret_cast<uintptr_t>(s0 + h) & 15u) == 0 && ((fo + h) & 3) == 0;
+    if constexpr (ADAM) vec_ok = vec_ok && (reinterpret_cast<uintptr_t>(s1 + h) & 15u) == 0;
+    vec_ok = vec_ok && (reinterpret_cast<uintptr_t>(g + h) & (sizeof(gvec) - 1)) == 0;
+    if constexpr (MODEL) vec_ok = vec_ok && (reinterpret_cast<uintptr_t>(mdl + h) & 7u) == 0;
+    if (!vec_ok) {
+        for (int i = tid; i < n; i += kThreads) one(i);
+    } else {
+        if (tid < h) one(tid);
+        const int nv = (n - h) >> 2;
+        const int tail0 = h + 4 * nv;
+        if (tid < n - tail0) one(tail0 + tid);
+        f32x4 *p4 = reinterpret_cast<f32x4 *>(p + h);
+        f32x4 *a4 = reinterpret_cast<f32x4 *>(s0 + h);
+        f32x4 *b4 = reinterpret_cast<f32x4 *>(s1 + h);
+        const gvec *g4 = reinterpret_cast<const gvec *>(g + h);
+        u16x4 *m4 = reinterpret_cast<u16x4 *>(mdl + h);
+        auto stats4 = [&](f32x4 m, f32x4 x) {
+            const f32x4 d = m - x;
+            gsum += (double)d.x * (double)d.x;
+            gsum += (double)d.y * (double)d.y;
+            gsum += (double)d.z * (double)d.z;
+            gsum += (double)d.w * (double)d.w;
+        };
+        auto finish = [&](int v, f32x4 m, gvec gv, f32x4 av, f32x4 bv) {
+            if constexpr (STATS) {
+                msum += (double)m.x * (double)m.x;
+                msum += (double)m.y * (double)m.y;
+                msum += (double)m.z * (double)m.z;
+                msum += (double)m.w * (double)m.w;
+            }
+            const f32x4 gw = G::widen(gv);
+            float G4[4] = {gw.x, gw.y, gw.z, gw.w};
+            float P4[4] = {m.x, m.y, m.z, m.w};
+            float A4[4] = {av.x, av.y, av.z, av.w};
+            float B4[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (ADAM)
+                    adamw_one(G4[j], P4[j], A4[j], B4[j], s);
+                else
+                    sgdm_one(G4[j], P4[j], A4[j], s);
+            }
+            const f32x4 pn{P4[0], P4[1], P4[2], P4[3]};
+            st<NT>(p4 + v, pn);
+            st<NT>(a4 + v, f32x4{A4[0], A4[1], A4[2], A4[3]});
+            if constexpr (ADAM) st<NT>(b4 + v, f32x4{B4[0], B4[1], B4[2], B4[3]});
+            if constexpr (MODEL) st<NT>(m4 + v, bf16_rne4(pn));
+        };
+        if constexpr (NREP > 0) {
+            const f32x4 *x4[NREP];
+#pragma unroll
+            for (int k = 0; k < NREP; ++k) x4[k] = reinterpret_cast<const f32x4 *>(src(k) + h);
+            for (int v = tid; v < nv; v += kThreads) {
+                f32x4 x[NREP];
+#pragma unroll
+                for (int k = 0; k < NREP; ++k) x[k] = ld<NT>(x4[k] + v);
+                const gvec gv = ld<NT>(g4 + v);
+                const f32x4 av = ld<NT>(a4 + v);
+                f32x4 bv{};
+                if constexpr (ADAM) bv = ld<NT>(b4 + v);
+                f32x4 acc = x[0];
+#pragma unroll
+                for (int k = 1; k < NREP; ++k) acc = acc + x[k];
+                const f32x4 m = acc * inv_n;
+                if constexpr (STATS) {
+#pragma unroll
+                    for (int k = 0; k < NREP; ++k) stats4(m, x[k]);
+                }
+                finish(v, m, gv, av, bv);
+            }
+        } else {
+            for (int v = tid; v < nv; v += kThreads) {
+                f32x4 acc = ld<NT>(reinterpret_cast<const f32x4 *>(src(0) + h) + v);
+                for (int k = 1; k < nrep; ++k) acc = acc + ld<NT>(reinterpret_cast<const f32x4 *>(src(k) + h) + v);
+                const f32x4 m = acc * inv_n;
+                if constexpr (STATS) {
+                    for (int k = 0; k < nrep; ++k) stats4(m, reinterpret_cast<const f32x4 *>(src(k) + h)[v]);
+                }
+                const gvec gv = ld<NT>(g4 + v);
+                const f32x4 av = ld<NT>(a4 + v);
+                f32x4 bv{};
+                if constexpr (ADAM) bv = ld<NT>(b4 + v);
+                finish(v, m, gv, av, bv);
+            }
+        }
+    }
+    if constexpr (STATS) {
+        const double gt = block_sum(gsum, lds[0]);
+        const double mt = block_sum(msum, lds[1]);
+        if (tid == 0) {
+            const int64_t pi = (int64_t)a.tensor_chunk_base[ch.tensor] + ch.begin / a.chunk_elems;
+            a.partials[2 * pi] = gt;
+            a.partials[2 * pi + 1] = mt;
+        }
+    }
+}
+
 // lds_pad: bytes of dynamic LDS requested per workgroup although no kernel uses them.  A CU has 160 KiB, so the pad
 // caps how many workgroups are resident per CU, i.e. how wide the window of addresses in flight is.
 template <class K, class... Args>
@@ -535,7 +718,7 @@ int launch_mean(const MeanLaunch &a, void *stream) {
         default: rc = launch_mean_n<0>(ma, a, stream); break;
     }
     if (rc != 0 || !a.partials) return rc;
-    return launch(stats_finalize_kernel, a.n_layers, stream, 0, (const double *)a.partials, a.layer_chunk_ptr, a.n_replicas, a.stats);
+    return launch(stats_finalize_kernel, a.n_layers, stream, 0, (const double *)a.partials, a.layer_ranges, a.n_replicas, a.stats);
 }
 
 int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *tensors, const UpdateChunk *chunks, int64_t n_chunks,
@@ -555,6 +738,51 @@ int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *t
     DDP_UPD(true, true, true)
 #undef DDP_UPD
     return (int)hipErrorInvalidValue;
+}
+
+template <bool A, bool G, bool M>
+static int launch_fused_t(const FusedLaunch &f, const FusedArgs &fa, void *stream) {
+    const bool st = f.partials != nullptr;
+#define DDP_FUSED(NR)                                                                                        \
+    return st ? launch(fused_kernel<A, G, M, NR, true>, f.n_chunks, stream, f.lds_pad, fa)                   \
+              : launch(fused_kernel<A, G, M, NR, false>, f.n_chunks, stream, f.lds_pad, fa);
+    switch (f.n_replicas) {
+        case 4: DDP_FUSED(4)
+        case 8: DDP_FUSED(8)
+        case 16: DDP_FUSED(16)
+        default: DDP_FUSED(0)
+    }
+#undef DDP_FUSED
+}
+
+int launch_fused(const FusedLaunch &f, void *stream) {
+    FusedArgs fa{};
+    for (int k = 0; k < f.n_replicas; ++k) fa.x[k] = f.x[k];
+    fa.tensors = f.tensors;
+    fa.chunks = f.chunks;
+    fa.tensor_flat_off = f.tensor_flat_off;
+    fa.tensor_chunk_base = f.tensor_chunk_base;
+    fa.partials = f.partials;
+    fa.s = f.s;
+    fa.inv_n = f.inv_n;
+    fa.n = f.n_replicas;
+    fa.local_rank = f.local_rank;
+    fa.chunk_elems = f.chunk_elems;
+    const bool adam = f.kind == DDP_OPT_ADAMW, gb = f.grad_dtype == DDP_BF16, md = f.with_model;
+    int rc = (int)hipErrorInvalidValue;
+#define DDP_F(A, G, M) \
+    if (adam == A && gb == G && md == M) rc = launch_fused_t<A, G, M>(f, fa, stream);
+    DDP_F(false, false, false)
+    DDP_F(false, false, true)
+    DDP_F(false, true, false)
+    DDP_F(false, true, true)
+    DDP_F(true, false, false)
+    DDP_F(true, false, true)
+    DDP_F(true, true, false)
+    DDP_F(true, true, true)
+#undef DDP_F
+    if (rc != 0 || !f.partials) return rc;
+    return launch(stats_finalize_kernel, f.n_layers, stream, 0, (const double *)f.partials, f.layer_ranges, f.n_replicas, f.stats);
 }
 
 }  // namespace ddp

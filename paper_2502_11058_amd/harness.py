@@ -185,5 +185,11 @@ class DeviceReplica:
         c.ddp_unpack(slot, self.flat, stream)
         c.ddp_local_update(self.opt_struct(r + 1), stream)
 
+    def fused_step(self, r: int, local_rank: int = 0, with_stats: bool = True, stream=None) -> None:
+        """Iteration r through the fused entry point: same result, no flat round trip for the local replica."""
+        slot = r % len(self.sets)
+        self.ctx.ddp_fused_sync_update(slot, self.peers, len(self.peers) + 1, local_rank, self.stats if with_stats else None,
+                                       self.opt_struct(r + 1), stream)
+
     def close(self) -> None:
         self.ctx.close()

@@ -79,7 +79,7 @@ class Tally:
 
 
 def run_trajectory(oracle, w, policy=None, iters=None, arena_offset=0, options=None, order=0, grad_dtype=None,
-                   check_every=1, threads=16):
+                   check_every=1, threads=16, fused=False):
     from paper_2502_11058_amd.harness import DeviceReplica
     _need_gpu()
     oracle.set_threads(threads)
@@ -124,46 +124,66 @@ def run_trajectory(oracle, w, policy=None, iters=None, arena_offset=0, options=N
         assert lid.tolist() == list(S)
         ranges = wk.layer_ranges(S, off, order_t)
         assert lbeg.tolist() == [b for b, _ in ranges] + [total]
-        # pack: against an independent gather of the same device tensors (torch.cat in the oracle's order)
-        dev_flat = torch.cat([rep.sync[t] for t in order_t]) if total else rep.flat[:0]
-        local_host = _np(dev_flat)
-        rep.flat.fill_(float("nan"))
-        rep.ctx.ddp_pack(slot, rep.flat)
-        assert np.array_equal(_bits(_np(rep.flat[:total])), _bits(local_host)), f"pack r={r}"
-        assert np.array_equal(_bits(oracle.pack([_np(rep.sync[t]) for t in order_t], [off[t] for t in order_t], total)),
-                              _bits(local_host))
-        # peers: gathered local values + seeded drift; the same bytes go to both sides
-        rep.fill_peers_from(dev_flat, r, total)
-        peers_host = [_np(p[:total]) for p in rep.peers]
-        # average + statistics: bit-exact given the same inputs
-        out.fill_(float("nan"))
-        rep.stats.fill_(-1.0)
-        rep.ctx.ddp_partial_average(slot, rep.flat, rep.peers, N, rank, out, rep.stats)
-        reps = peers_host[:rank] + [local_host] + peers_host[rank:]
-        mean_ref = oracle.mean(reps) if total else local_host
-        assert np.array_equal(_bits(_np(out[:total])), _bits(mean_ref)), f"mean r={r}"
-        st = _np(rep.stats)
-        for i, (b, e) in enumerate(ranges):
-            g, m = oracle.layer_stats(reps, mean_ref, b, e)
-            assert st[2 * i] == pytest.approx(g, rel=1e-10, abs=1e-300), f"gamma r={r} layer {S[i]}"
-            assert st[2 * i + 1] == pytest.approx(m, rel=1e-10), f"msq r={r} layer {S[i]}"
-        # in-place variant (flat_out == flat_local) gives the same bits
-        rep.ctx.ddp_partial_average(slot, rep.flat, rep.peers, N, rank, rep.flat, None)
-        assert torch.equal(rep.flat[:total].view(torch.int32), out[:total].view(torch.int32)), f"in-place mean r={r}"
-        # unpack: the scheduled tensors now hold the average, the model copy its bf16 rounding, nothing else moved
-        before = rep.a_sync.clone()
-        rep.ctx.ddp_unpack(slot, out)
-        expect = before
-        for t in order_t:
-            expect[int(rep.offsets[t]): int(rep.offsets[t]) + rep.numel[t]] = out[int(off[t]): int(off[t]) + rep.numel[t]]
-        assert torch.equal(rep.a_sync.view(torch.int32), expect.view(torch.int32)), f"unpack r={r}"
-        if rep.bf16:
+        if fused:
+            # one call does average + update; peers from an independent gather, statistics and state against the oracle
+            dev_flat = torch.cat([rep.sync[t] for t in order_t]) if total else rep.flat[:0]
+            local_host = _np(dev_flat)
+            rep.fill_peers_from(dev_flat, r, total)
+            peers_host = [_np(p[:total]) for p in rep.peers]
+            rep.fill_grads(r)
+            grads = [_np(g) for g in rep.grad]
+            rep.stats.fill_(-1.0)
+            rep.ctx.ddp_fused_sync_update(slot, rep.peers, N, rank, rep.stats, rep.opt_struct(r + 1))
+            reps = peers_host[:rank] + [local_host] + peers_host[rank:]
+            mean_ref = oracle.mean(reps) if total else local_host
+            st = _np(rep.stats)
+            for i, (b, e) in enumerate(ranges):
+                g, m = oracle.layer_stats(reps, mean_ref, b, e)
+                assert st[2 * i] == pytest.approx(g, rel=1e-10, abs=1e-300), f"fused gamma r={r} layer {S[i]}"
+                assert st[2 * i + 1] == pytest.approx(m, rel=1e-10), f"fused msq r={r} layer {S[i]}"
+            wk.sync(S, peers_host, rank)
+            wk.local_update(grads, r + 1)
+        else:
+            # pack: against an independent gather of the same device tensors (torch.cat in the oracle's order)
+            dev_flat = torch.cat([rep.sync[t] for t in order_t]) if total else rep.flat[:0]
+            local_host = _np(dev_flat)
+            rep.flat.fill_(float("nan"))
+            rep.ctx.ddp_pack(slot, rep.flat)
+            assert np.array_equal(_bits(_np(rep.flat[:total])), _bits(local_host)), f"pack r={r}"
+            assert np.array_equal(_bits(oracle.pack([_np(rep.sync[t]) for t in order_t], [off[t] for t in order_t], total)),
+                                  _bits(local_host))
+            # peers: gathered local values + seeded drift; the same bytes go to both sides
+            rep.fill_peers_from(dev_flat, r, total)
+            peers_host = [_np(p[:total]) for p in rep.peers]
+            # average + statistics: bit-exact given the same inputs
+            out.fill_(float("nan"))
+            rep.stats.fill_(-1.0)
+            rep.ctx.ddp_partial_average(slot, rep.flat, rep.peers, N, rank, out, rep.stats)
+            reps = peers_host[:rank] + [local_host] + peers_host[rank:]
+            mean_ref = oracle.mean(reps) if total else local_host
+            assert np.array_equal(_bits(_np(out[:total])), _bits(mean_ref)), f"mean r={r}"
+            st = _np(rep.stats)
+            for i, (b, e) in enumerate(ranges):
+                g, m = oracle.layer_stats(reps, mean_ref, b, e)
+                assert st[2 * i] == pytest.approx(g, rel=1e-10, abs=1e-300), f"gamma r={r} layer {S[i]}"
+                assert st[2 * i + 1] == pytest.approx(m, rel=1e-10), f"msq r={r} layer {S[i]}"
+            # in-place variant (flat_out == flat_local) gives the same bits
+            rep.ctx.ddp_partial_average(slot, rep.flat, rep.peers, N, rank, rep.flat, None)
+            assert torch.equal(rep.flat[:total].view(torch.int32), out[:total].view(torch.int32)), f"in-place mean r={r}"
+            # unpack: the scheduled tensors now hold the average, the model copy its bf16 rounding, nothing else moved
+            before = rep.a_sync.clone()
+            rep.ctx.ddp_unpack(slot, out)
+            expect = before
             for t in order_t:
-                assert np.array_equal(_np(rep.model[t]), oracle.bf16_rne(mean_ref[int(off[t]): int(off[t]) + rep.numel[t]])), f"model copy r={r} t={t}"
-        # the carried oracle worker takes the same step from its own state
-        wk.sync(S, peers_host, rank)
-        if order == 0:
-            update_both(r)
+                expect[int(rep.offsets[t]): int(rep.offsets[t]) + rep.numel[t]] = out[int(off[t]): int(off[t]) + rep.numel[t]]
+            assert torch.equal(rep.a_sync.view(torch.int32), expect.view(torch.int32)), f"unpack r={r}"
+            if rep.bf16:
+                for t in order_t:
+                    assert np.array_equal(_np(rep.model[t]), oracle.bf16_rne(mean_ref[int(off[t]): int(off[t]) + rep.numel[t]])), f"model copy r={r} t={t}"
+            # the carried oracle worker takes the same step from its own state
+            wk.sync(S, peers_host, rank)
+            if order == 0:
+                update_both(r)
         if (r + 1) % check_every == 0 or r == iters - 1:
             for t in range(len(rep.sync)):
                 gp, gs0 = _np(rep.sync[t]), _np(rep.s0[t])
@@ -234,6 +254,23 @@ def test_small_llama_bubble_filled_schedule(oracle):
     assert sum(len(S) for S in sets) > w.n_layers          # some layer really is synchronised twice per period
     t = run_trajectory(oracle, w, policy="enp+fill", iters=8)
     assert t.frac() == 1.0
+
+
+@pytest.mark.parametrize("name,kw", [("tiny", {}), ("small_llama", {}), ("small_llama", {"n_replicas": 5, "period": 3}),
+                                     ("small_llama", {"n_replicas": 16})])
+def test_fused_sync_update_equals_the_four_calls(oracle, name, kw):
+    w = W.WORKLOADS[name](**kw)
+    t = run_trajectory(oracle, w, fused=True, iters=8)
+    assert t.frac() == 1.0
+
+
+@pytest.mark.parametrize("arena_offset", [0, 1, 3])
+def test_fused_odd_shapes(oracle, arena_offset):
+    w = W.odd(optimizer="adamw", param_dtype="bf16", n_replicas=4, period=2)
+    t = run_trajectory(oracle, w, fused=True, arena_offset=arena_offset, options={"update_chunk": 1024})
+    assert t.frac() == 1.0
+    w = W.odd(optimizer="sgdm", param_dtype="f32", n_replicas=3, period=3)
+    run_trajectory(oracle, w, fused=True, arena_offset=arena_offset, policy="full")
 
 
 def test_single_replica_is_identity(oracle):
