@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 
 # HBM bytes per launch of the update kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what
 # the same counters read for a plain copy of known size (profiles/llama2_7b_step_kernels.txt); None if not measured.
-MEASURED_TRAFFIC_BYTES = {"llama2_7b": 188.781e9}
+MEASURED_TRAFFIC_BYTES = {"llama2_7b": 189.099e9}
 
 
 def algorithmic_bytes(w, S: int):
