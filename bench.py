@@ -100,6 +100,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 4 plain elementwise copies of 1 GiB (torch.add(src, 0, out=dst)) before the timed region, "
                          "as the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--placement-study", type=int, default=0, metavar="M",
+                    help="instead of the benchmark: allocate the slab M times in a row, time the update kernel on each "
+                         "(zeroed state) and print the GB/s list; shows the two physical placements a slab alternates between")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (peers are staged in HBM; there are no collectives). "
@@ -115,6 +118,20 @@ def main() -> int:
         return 3
     w = W.get(args.workload)
     options = {k: int(v) for k, v in (o.split("=") for o in args.option)}
+    if args.placement_study:
+        import gc
+        res = []
+        for _ in range(args.placement_study):
+            rep = DeviceReplica(w, 0, options=options, policy=args.policy, placement_probe=False)
+            res.append(round(rep._probe(), 1))
+            rep.close()
+            rep._release()
+            rep.ctx.close()
+            del rep
+            gc.collect()
+            torch.cuda.empty_cache()
+        print(json.dumps({"placement_study_update_GBps": res, "workload": w.name}))
+        return 0
     rep = DeviceReplica(w, 0, options=options, policy=args.policy)
     rep.init_params()
     rep.fill_grads(0)
