@@ -40,7 +40,7 @@ def _sample_positions(rep, n_random, seed):
     return np.unique(np.concatenate(pos)) + int(rep.offsets[0])
 
 
-def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000):
+def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000, fused=False):
     from paper_2502_11058_amd.harness import DeviceReplica
     _need_gpu()
     oracle.set_threads(16)
@@ -76,6 +76,40 @@ def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000)
         g_s = _np(rep.a_grad[gi])
         base = torch.cat([rep.sync[t] for t in order_t])       # independent gather (harness), the peers' base
         rep.fill_peers_from(base, r, total)
+        if fused:
+            # one launch: only the end state and the statistics are observable
+            x_s = [_np(p[fi]) for p in rep.peers]
+            reps_s = x_s[:rank] + [_np(base[fi])] + x_s[rank:]
+            mean_s = oracle.mean(reps_s)
+            unsched_before = None
+            i = int(np.argmin([int(lbeg[j + 1] - lbeg[j]) for j in range(len(S))]))
+            b, e = int(lbeg[i]), int(lbeg[i + 1])
+            layer_reps = None
+            if e - b <= stats_layer_cap:
+                xs = [_np(p[b:e]) for p in rep.peers]
+                layer_reps = xs[:rank] + [_np(base[b:e])] + xs[rank:]
+            del base
+            rep.stats.fill_(-1.0)
+            rep.ctx.ddp_fused_sync_update(slot, rep.peers, N, rank, rep.stats, rep.opt_struct(r + 1))
+            if layer_reps is not None:
+                st = _np(rep.stats)
+                g, m = oracle.layer_stats(layer_reps, oracle.mean(layer_reps), 0, e - b)
+                assert st[2 * i] == pytest.approx(g, rel=1e-10), f"fused gamma r={r} layer {S[i]}"
+                assert st[2 * i + 1] == pytest.approx(m, rel=1e-10), f"fused msq r={r} layer {S[i]}"
+                del layer_reps, xs
+            p_s[sel_host] = mean_s
+            model_s[sel_host] = oracle.bf16_rne(mean_s)
+            oracle.adamw(p_s, g_s, m_s, v_s, model_s, w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, r + 1)
+            gp, gm, gv = _np(rep.a_sync[gi]), _np(rep.a_s0[gi]), _np(rep.a_s1[gi])
+            assert_close_fp32(gp, p_s, f"fused param r={r}", 1e-9)
+            assert_close_fp32(gm, m_s, f"fused m r={r}", 1e-12)
+            assert_close_fp32(gv, v_s, f"fused v r={r}", 1e-16)
+            assert_bf16_within_one_ulp(_np(rep.a_model[gi]), model_s, f"fused model r={r}")
+            for a_, b_ in ((gp, p_s), (gm, m_s), (gv, v_s)):
+                n_total += a_.size
+                n_exact += int((_bits(a_) == _bits(b_)).sum())
+            progress(f"[{w.name}] fused r={r} slot {slot} ({total} elements) ok")
+            continue
         # pack: every element against the gather
         rep.flat.fill_(float("nan"))
         rep.ctx.ddp_pack(slot, rep.flat)
@@ -153,6 +187,11 @@ def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000)
 @pytest.mark.timeout(1500)
 def test_llama2_7b_sampled_trajectory(oracle):
     assert run_sampled(oracle, W.llama2_7b(), iters=8) == 1.0
+
+
+@pytest.mark.timeout(1500)
+def test_llama2_7b_fused_sampled_trajectory(oracle):
+    assert run_sampled(oracle, W.llama2_7b(), iters=8, fused=True) == 1.0
 
 
 @pytest.mark.timeout(1500)
