@@ -12,7 +12,7 @@ from typing import List, Optional, Sequence, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "lib", "libdreamddp.so")
+LIB_PATH = os.environ.get("DREAMDDP_LIB") or os.path.join(_HERE, "lib", "libdreamddp.so")
 
 DDP_F32, DDP_BF16 = 0, 1
 DDP_OPT_SGDM, DDP_OPT_ADAMW = 0, 1
