@@ -59,6 +59,7 @@ static void drop_schedule(ddp_ctx *c) {
     c->H = 0;
     if (c->d_partials) (void)hipFree(c->d_partials);
     c->d_partials = nullptr;
+    c->d_slice_sums = nullptr;
     c->partials_cap = 0;
 }
 
@@ -327,13 +328,14 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
     }
     max_mean_chunks = std::max(max_mean_chunks, ctx->n_update);  // the fused step keeps one partial per update chunk
     if (max_mean_chunks > 0) {
-        hipError_t e = hipMalloc((void **)&ctx->d_partials, (size_t)max_mean_chunks * 2 * sizeof(double));
+        hipError_t e = hipMalloc((void **)&ctx->d_partials, ((size_t)max_mean_chunks + (size_t)ctx->L * 64) * 2 * sizeof(double));
         if (e != hipSuccess) {
             ctx->d_partials = nullptr;
             for (auto &x : slots) free_slot(x);
             return fail(ctx, DDP_ENOMEM, std::string("ddp_set_schedule: hipMalloc of the reduction scratch failed: ") + hipGetErrorString(e));
         }
         ctx->partials_cap = max_mean_chunks;
+        ctx->d_slice_sums = ctx->d_partials + 2 * max_mean_chunks;
     }
     ctx->slots = std::move(slots);
     ctx->H = H;
@@ -454,6 +456,7 @@ extern "C" int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_loc
     a.chunks = s->d_mean;
     a.n_chunks = s->n_mean;
     a.partials = layer_stats ? ctx->d_partials : nullptr;
+    a.slice_sums = ctx->d_slice_sums;
     a.layer_ranges = s->d_layer_ranges;
     a.n_layers = (int)s->layers.size();
     a.stats = layer_stats;
@@ -536,6 +539,7 @@ extern "C" int ddp_fused_sync_update(ddp_ctx *ctx, int slot, const float *const 
     f.chunk_elems = (int)ctx->update_chunk;
     f.s = s;
     f.partials = (layer_stats && !st->layers.empty()) ? ctx->d_partials : nullptr;
+    f.slice_sums = ctx->d_slice_sums;
     f.layer_ranges = st->d_fused_ranges;
     f.n_layers = (int)st->layers.size();
     f.stats = layer_stats;

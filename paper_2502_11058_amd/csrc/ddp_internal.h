@@ -73,6 +73,7 @@ struct MeanLaunch {
     const MeanChunk *chunks;
     int64_t n_chunks;
     double *partials;  // [n_chunks][2] or nullptr when no statistics are wanted
+    double *slice_sums;  // [n_layers][64][2] scratch of the two-stage reduction
     const int32_t *layer_ranges;  // per layer [first, last) partial index
     int n_layers;
     double *stats;  // [n_layers][2]
@@ -102,6 +103,7 @@ struct FusedLaunch {
     int chunk_elems;
     UpdateScalars s;
     double *partials;  // nullptr: no statistics
+    double *slice_sums;
     const int32_t *layer_ranges;
     int n_layers;
     double *stats;
@@ -138,7 +140,8 @@ struct ddp_ctx {
     // schedule
     int H = 0;
     std::vector<ddp::SlotTables> slots;
-    double *d_partials = nullptr;  // reduction scratch for per-layer statistics, sized for the largest slot
+    double *d_partials = nullptr;  // reduction scratch for per-layer statistics: one partial pair per chunk ...
+    double *d_slice_sums = nullptr;  // ... followed by 64 slice sums per layer (same allocation)
     int64_t partials_cap = 0;
 };
 

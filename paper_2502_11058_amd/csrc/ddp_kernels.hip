@@ -319,23 +319,40 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
     }
 }
 
-// Per layer: add the chunk partials of that layer in a fixed order (thread-strided, then the workgroup tree) and
-// scale the divergence by 1/N (Sec. 3.4: Gamma = 1/K sum_k ||wbar - w^k||^2, here per layer).  Layer l owns the
-// partials [ranges[2l], ranges[2l+1]).
-__global__ __launch_bounds__(kThreads) void stats_finalize_kernel(const double *__restrict__ partials,
-                                                                  const int32_t *__restrict__ ranges, int n_replicas,
-                                                                  double *__restrict__ stats) {
+// Per-layer statistics from the per-chunk partials, in two fixed-order stages so that a layer with 10^5 chunks does
+// not hang on one workgroup: stage 1 cuts layer l's partials [ranges[2l], ranges[2l+1]) into kStatSlices contiguous
+// slices, one workgroup each (thread-strided sums, then the workgroup tree); stage 2 adds the slice sums of a layer
+// in slice order and scales the divergence by 1/N (Sec. 3.4: Gamma = 1/K sum_k ||wbar - w^k||^2, per layer).
+constexpr int kStatSlices = 64;
+
+__global__ __launch_bounds__(kThreads) void stats_slices_kernel(const double *__restrict__ partials,
+                                                                const int32_t *__restrict__ ranges, double *__restrict__ slice_sums) {
     __shared__ double lds[2][kThreads / kWave];
-    const int l = blockIdx.x;
-    const int c0 = ranges[2 * l], c1 = ranges[2 * l + 1];
+    const int l = blockIdx.y, j = blockIdx.x;
+    const int64_t c0 = ranges[2 * l], c1 = ranges[2 * l + 1];
+    const int64_t lo = c0 + (c1 - c0) * j / kStatSlices, hi = c0 + (c1 - c0) * (j + 1) / kStatSlices;
     double g = 0.0, m = 0.0;
-    for (int c = c0 + (int)threadIdx.x; c < c1; c += kThreads) {
-        g += partials[2 * (int64_t)c];
-        m += partials[2 * (int64_t)c + 1];
+    for (int64_t c = lo + (int64_t)threadIdx.x; c < hi; c += kThreads) {
+        g += partials[2 * c];
+        m += partials[2 * c + 1];
     }
     g = block_sum(g, lds[0]);
     m = block_sum(m, lds[1]);
     if (threadIdx.x == 0) {
+        slice_sums[2 * ((int64_t)l * kStatSlices + j)] = g;
+        slice_sums[2 * ((int64_t)l * kStatSlices + j) + 1] = m;
+    }
+}
+
+__global__ __launch_bounds__(kWave) void stats_finalize_kernel(const double *__restrict__ slice_sums, int n_replicas,
+                                                               double *__restrict__ stats) {
+    const int l = blockIdx.x;
+    if (threadIdx.x == 0) {
+        double g = 0.0, m = 0.0;
+        for (int j = 0; j < kStatSlices; ++j) {
+            g += slice_sums[2 * ((int64_t)l * kStatSlices + j)];
+            m += slice_sums[2 * ((int64_t)l * kStatSlices + j) + 1];
+        }
         stats[2 * l] = g / (double)n_replicas;
         stats[2 * l + 1] = m;
     }
@@ -685,6 +702,18 @@ int launch(K kernel, int64_t grid, void *stream, int lds_pad, Args... args) {
     return (int)hipGetLastError();
 }
 
+int launch_stats(const double *partials, double *slice_sums, const int32_t *ranges, int n_layers, int n_replicas, double *stats,
+                 void *stream) {
+    if (n_layers <= 0) return 0;
+    hipLaunchKernelGGL(stats_slices_kernel, dim3(kStatSlices, (unsigned)n_layers), dim3(kThreads), 0, (hipStream_t)stream, partials,
+                       ranges, slice_sums);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+    hipLaunchKernelGGL(stats_finalize_kernel, dim3((unsigned)n_layers), dim3(kWave), 0, (hipStream_t)stream,
+                       (const double *)slice_sums, n_replicas, stats);
+    return (int)hipGetLastError();
+}
+
 template <int NREP>
 int launch_mean_n(const MeanArgs &ma, const MeanLaunch &a, void *stream) {
     if (a.partials) return a.nontemporal ? launch(mean_kernel<NREP, true, true>, a.n_chunks, stream, a.lds_pad, ma) : launch(mean_kernel<NREP, true, false>, a.n_chunks, stream, a.lds_pad, ma);
@@ -725,7 +754,7 @@ int launch_mean(const MeanLaunch &a, void *stream) {
         default: rc = launch_mean_n<0>(ma, a, stream); break;
     }
     if (rc != 0 || !a.partials) return rc;
-    return launch(stats_finalize_kernel, a.n_layers, stream, 0, (const double *)a.partials, a.layer_ranges, a.n_replicas, a.stats);
+    return launch_stats(a.partials, a.slice_sums, a.layer_ranges, a.n_layers, a.n_replicas, a.stats, stream);
 }
 
 int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *tensors, const UpdateChunk *chunks, int64_t n_chunks,
@@ -789,7 +818,7 @@ int launch_fused(const FusedLaunch &f, void *stream) {
     DDP_F(true, true, true)
 #undef DDP_F
     if (rc != 0 || !f.partials) return rc;
-    return launch(stats_finalize_kernel, f.n_layers, stream, 0, (const double *)f.partials, f.layer_ranges, f.n_replicas, f.stats);
+    return launch_stats(f.partials, f.slice_sums, f.layer_ranges, f.n_layers, f.n_replicas, f.stats, stream);
 }
 
 }  // namespace ddp

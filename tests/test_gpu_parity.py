@@ -5,6 +5,7 @@ bit-exact; per-layer statistics agree to 1e-10 relative (fp64 sums in a differen
 agree within 1e-6 relative (fp32) and the bf16 model copy within 1 bf16 ulp, after every iteration.
 """
 import os
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
@@ -163,8 +164,9 @@ def run_trajectory(oracle, w, policy=None, iters=None, arena_offset=0, options=N
             mean_ref = oracle.mean(reps) if total else local_host
             assert np.array_equal(_bits(_np(out[:total])), _bits(mean_ref)), f"mean r={r}"
             st = _np(rep.stats)
-            for i, (b, e) in enumerate(ranges):
-                g, m = oracle.layer_stats(reps, mean_ref, b, e)
+            with ThreadPoolExecutor(max_workers=8) as pool:      # one oracle call per layer; ctypes releases the GIL
+                ref_stats = list(pool.map(lambda be: oracle.layer_stats(reps, mean_ref, be[0], be[1]), ranges))
+            for i, (g, m) in enumerate(ref_stats):
                 assert st[2 * i] == pytest.approx(g, rel=1e-10, abs=1e-300), f"gamma r={r} layer {S[i]}"
                 assert st[2 * i + 1] == pytest.approx(m, rel=1e-10), f"msq r={r} layer {S[i]}"
             # in-place variant (flat_out == flat_local) gives the same bits
