@@ -117,11 +117,17 @@ int ddp_schedule_time_model(int L, int H, const int64_t *t_fp_ns, const int64_t 
 int ddp_create(ddp_ctx **out, int device);
 int ddp_destroy(ddp_ctx *ctx);
 
-/* Tuning knobs, to be set before ddp_register_model / ddp_set_schedule (they shape the tables built there):
- *   "update_chunk", "mean_chunk", "copy_chunk"  elements per workgroup (multiple of 1024, 1024..1048576)
- *   "nontemporal"                               0/1: streaming cache hints on loads and stores
- *   "dispatch_ways"                             1..4096: launch order of the workgroups; w > 1 cuts every chunk table
- *                                               into w contiguous segments and visits them round-robin
+/* Tuning knobs.  The first two groups shape the tables built by ddp_register_model / ddp_set_schedule and must be
+ * set before them (DDP_ESTATE otherwise); the others take effect at the next launch.
+ *   "update_chunk", "mean_chunk", "copy_chunk"  elements per workgroup (multiple of 1024, 1024..1048576;
+ *                                               defaults 2048 / 1024 / 2048)
+ *   "dispatch_ways"                             1..4096 (default 1): launch order of the workgroups; w > 1 cuts every
+ *                                               chunk table into w contiguous segments and visits them round-robin
+ *   "update_lds", "mean_lds", "copy_lds"        0..65536 bytes of dynamic LDS requested per workgroup without being
+ *                                               used: caps the workgroups resident per CU (160 KiB of LDS each), which
+ *                                               keeps the window of DRAM rows in flight narrow (defaults 65536 / 53248 /
+ *                                               24576 = 2 / 3 / 6 workgroups per CU)
+ *   "nontemporal"                               0/1 (default 1): streaming cache hints on loads and stores
  * Unknown names or bad values: DDP_EINVAL. */
 int ddp_set_option(ddp_ctx *ctx, const char *name, int64_t value);
 

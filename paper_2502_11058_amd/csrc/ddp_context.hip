@@ -4,6 +4,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <exception>
 #include <new>
 #include <string>
 #include <vector>
@@ -174,172 +175,188 @@ extern "C" int ddp_set_option(ddp_ctx *ctx, const char *name, int64_t value) {
 extern "C" int ddp_register_model(ddp_ctx *ctx, int L, int T, const int32_t *layer_of, const int64_t *numel, int param_dtype,
                                   int grad_dtype, void *const *sync_ptr, void *const *model_ptr, void *const *grad_ptr,
                                   void *const *state0_ptr, void *const *state1_ptr) {
-    if (!ctx) return fail(nullptr, DDP_EINVAL, "ddp_register_model: ctx is NULL");
-    if (L < 1 || T < L) return fail(ctx, DDP_EINVAL, "ddp_register_model: need L >= 1 and T >= L");
-    if (!layer_of || !numel || !sync_ptr || !grad_ptr || !state0_ptr) return fail(ctx, DDP_EINVAL, "ddp_register_model: NULL array");
-    if (param_dtype != DDP_F32 && param_dtype != DDP_BF16) return fail(ctx, DDP_EINVAL, "ddp_register_model: bad param_dtype");
-    if (grad_dtype != DDP_F32 && grad_dtype != DDP_BF16) return fail(ctx, DDP_EINVAL, "ddp_register_model: bad grad_dtype");
-    if (param_dtype == DDP_BF16 && !model_ptr) return fail(ctx, DDP_EINVAL, "ddp_register_model: bf16 params need model_ptr");
-    int rc = check_device(ctx, "ddp_register_model");
-    if (rc != DDP_OK) return rc;
+    try {
+        if (!ctx) return fail(nullptr, DDP_EINVAL, "ddp_register_model: ctx is NULL");
+        if (L < 1 || T < L) return fail(ctx, DDP_EINVAL, "ddp_register_model: need L >= 1 and T >= L");
+        if (!layer_of || !numel || !sync_ptr || !grad_ptr || !state0_ptr) return fail(ctx, DDP_EINVAL, "ddp_register_model: NULL array");
+        if (param_dtype != DDP_F32 && param_dtype != DDP_BF16) return fail(ctx, DDP_EINVAL, "ddp_register_model: bad param_dtype");
+        if (grad_dtype != DDP_F32 && grad_dtype != DDP_BF16) return fail(ctx, DDP_EINVAL, "ddp_register_model: bad grad_dtype");
+        if (param_dtype == DDP_BF16 && !model_ptr) return fail(ctx, DDP_EINVAL, "ddp_register_model: bf16 params need model_ptr");
+        int rc = check_device(ctx, "ddp_register_model");
+        if (rc != DDP_OK) return rc;
 
-    std::vector<TensorDesc> ts((size_t)T);
-    std::vector<int32_t> first((size_t)L + 1, 0);
-    const uintptr_t galign = grad_dtype == DDP_F32 ? 4 : 2;
-    for (int t = 0; t < T; ++t) {
-        const std::string tn = "tensor " + std::to_string(t);
-        if (layer_of[t] < 0 || layer_of[t] >= L) return fail(ctx, DDP_EINVAL, "ddp_register_model: " + tn + " has a layer id out of range");
-        if (t == 0 ? layer_of[t] != 0 : (layer_of[t] != layer_of[t - 1] && layer_of[t] != layer_of[t - 1] + 1))
-            return fail(ctx, DDP_EINVAL, "ddp_register_model: layer_of must be non-decreasing and cover 0..L-1 (" + tn + ")");
-        if (numel[t] <= 0) return fail(ctx, DDP_ESHAPE, "ddp_register_model: " + tn + " has numel <= 0");
-        if (!sync_ptr[t] || !grad_ptr[t] || !state0_ptr[t]) return fail(ctx, DDP_EINVAL, "ddp_register_model: " + tn + " has a NULL pointer");
-        if (param_dtype == DDP_BF16 && !model_ptr[t]) return fail(ctx, DDP_EINVAL, "ddp_register_model: " + tn + " lacks its bf16 model copy");
-        if (!aligned(sync_ptr[t], 4) || !aligned(state0_ptr[t], 4) || !aligned(grad_ptr[t], galign) ||
-            (state1_ptr && state1_ptr[t] && !aligned(state1_ptr[t], 4)) ||
-            (param_dtype == DDP_BF16 && !aligned(model_ptr[t], 2)))
-            return fail(ctx, DDP_EALIGN, "ddp_register_model: " + tn + " is not aligned to its element type");
-        TensorDesc &d = ts[(size_t)t];
-        d.sync = (float *)sync_ptr[t];
-        d.model = param_dtype == DDP_BF16 ? (uint16_t *)model_ptr[t] : nullptr;
-        d.grad = grad_ptr[t];
-        d.state0 = (float *)state0_ptr[t];
-        d.state1 = state1_ptr ? (float *)state1_ptr[t] : nullptr;
-        d.numel = numel[t];
-        first[(size_t)layer_of[t] + 1] = t + 1;
-    }
-    if (layer_of[T - 1] != L - 1) return fail(ctx, DDP_EINVAL, "ddp_register_model: layer_of does not reach L-1");
-    bool has1 = state1_ptr != nullptr;
-    if (has1)
-        for (int t = 0; t < T; ++t) has1 = has1 && state1_ptr[t] != nullptr;
-
-    drop_model(ctx);
-    ctx->L = L;
-    ctx->T = T;
-    ctx->param_dtype = param_dtype;
-    ctx->grad_dtype = grad_dtype;
-    ctx->has_state1 = has1;
-    ctx->layer_of.assign(layer_of, layer_of + T);
-    ctx->numel.assign(numel, numel + T);
-    ctx->tensors = ts;
-    ctx->layer_first_tensor = first;
-
-    // update table: every tensor cut into runs of update_chunk elements
-    std::vector<UpdateChunk> uc;
-    ctx->tensor_chunk_base.assign((size_t)T + 1, 0);
-    for (int t = 0; t < T; ++t) {
-        ctx->tensor_chunk_base[(size_t)t] = (int32_t)uc.size();
-        for (int64_t b = 0; b < numel[t]; b += ctx->update_chunk) {
-            int64_t n = std::min<int64_t>(ctx->update_chunk, numel[t] - b);
-            uc.push_back({b, t, (int32_t)n});
+        std::vector<TensorDesc> ts((size_t)T);
+        std::vector<int32_t> first((size_t)L + 1, 0);
+        const uintptr_t galign = grad_dtype == DDP_F32 ? 4 : 2;
+        for (int t = 0; t < T; ++t) {
+            const std::string tn = "tensor " + std::to_string(t);
+            if (layer_of[t] < 0 || layer_of[t] >= L) return fail(ctx, DDP_EINVAL, "ddp_register_model: " + tn + " has a layer id out of range");
+            if (t == 0 ? layer_of[t] != 0 : (layer_of[t] != layer_of[t - 1] && layer_of[t] != layer_of[t - 1] + 1))
+                return fail(ctx, DDP_EINVAL, "ddp_register_model: layer_of must be non-decreasing and cover 0..L-1 (" + tn + ")");
+            if (numel[t] <= 0) return fail(ctx, DDP_ESHAPE, "ddp_register_model: " + tn + " has numel <= 0");
+            if (!sync_ptr[t] || !grad_ptr[t] || !state0_ptr[t]) return fail(ctx, DDP_EINVAL, "ddp_register_model: " + tn + " has a NULL pointer");
+            if (param_dtype == DDP_BF16 && !model_ptr[t]) return fail(ctx, DDP_EINVAL, "ddp_register_model: " + tn + " lacks its bf16 model copy");
+            if (!aligned(sync_ptr[t], 4) || !aligned(state0_ptr[t], 4) || !aligned(grad_ptr[t], galign) ||
+                (state1_ptr && state1_ptr[t] && !aligned(state1_ptr[t], 4)) ||
+                (param_dtype == DDP_BF16 && !aligned(model_ptr[t], 2)))
+                return fail(ctx, DDP_EALIGN, "ddp_register_model: " + tn + " is not aligned to its element type");
+            TensorDesc &d = ts[(size_t)t];
+            d.sync = (float *)sync_ptr[t];
+            d.model = param_dtype == DDP_BF16 ? (uint16_t *)model_ptr[t] : nullptr;
+            d.grad = grad_ptr[t];
+            d.state0 = (float *)state0_ptr[t];
+            d.state1 = state1_ptr ? (float *)state1_ptr[t] : nullptr;
+            d.numel = numel[t];
+            first[(size_t)layer_of[t] + 1] = t + 1;
         }
-    }
-    ctx->tensor_chunk_base[(size_t)T] = (int32_t)uc.size();
-    ctx->n_update = (int64_t)uc.size();
-    interleave_segments(uc, ctx->dispatch_ways);
-    rc = upload(ctx, ts, &ctx->d_tensors);
-    if (rc == DDP_OK) rc = upload(ctx, uc, &ctx->d_update);
-    if (rc == DDP_OK) rc = upload(ctx, ctx->tensor_chunk_base, &ctx->d_tensor_chunk_base);
-    if (rc != DDP_OK) {
+        if (layer_of[T - 1] != L - 1) return fail(ctx, DDP_EINVAL, "ddp_register_model: layer_of does not reach L-1");
+        bool has1 = state1_ptr != nullptr;
+        if (has1)
+            for (int t = 0; t < T; ++t) has1 = has1 && state1_ptr[t] != nullptr;
+
         drop_model(ctx);
-        return rc;
+        ctx->L = L;
+        ctx->T = T;
+        ctx->param_dtype = param_dtype;
+        ctx->grad_dtype = grad_dtype;
+        ctx->has_state1 = has1;
+        ctx->layer_of.assign(layer_of, layer_of + T);
+        ctx->numel.assign(numel, numel + T);
+        ctx->tensors = ts;
+        ctx->layer_first_tensor = first;
+
+        // update table: every tensor cut into runs of update_chunk elements
+        std::vector<UpdateChunk> uc;
+        ctx->tensor_chunk_base.assign((size_t)T + 1, 0);
+        for (int t = 0; t < T; ++t) {
+            ctx->tensor_chunk_base[(size_t)t] = (int32_t)uc.size();
+            for (int64_t b = 0; b < numel[t]; b += ctx->update_chunk) {
+                int64_t n = std::min<int64_t>(ctx->update_chunk, numel[t] - b);
+                uc.push_back({b, t, (int32_t)n});
+            }
+        }
+        if (uc.size() > (size_t)0x7fffffff) {
+            drop_model(ctx);
+            return fail(ctx, DDP_ESHAPE, "ddp_register_model: more than 2^31-1 update chunks; raise update_chunk");
+        }
+        ctx->tensor_chunk_base[(size_t)T] = (int32_t)uc.size();
+        ctx->n_update = (int64_t)uc.size();
+        interleave_segments(uc, ctx->dispatch_ways);
+        rc = upload(ctx, ts, &ctx->d_tensors);
+        if (rc == DDP_OK) rc = upload(ctx, uc, &ctx->d_update);
+        if (rc == DDP_OK) rc = upload(ctx, ctx->tensor_chunk_base, &ctx->d_tensor_chunk_base);
+        if (rc != DDP_OK) {
+            drop_model(ctx);
+            return rc;
+        }
+        ctx->n_update = (int64_t)uc.size();
+        ctx->registered = true;
+        return DDP_OK;
+    } catch (const std::exception &e) {
+        return fail(ctx, DDP_ENOMEM, std::string("ddp_register_model: host allocation failed: ") + e.what());
     }
-    ctx->n_update = (int64_t)uc.size();
-    ctx->registered = true;
-    return DDP_OK;
 }
 
 extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, const int32_t *set_layers) {
-    if (!ctx) return fail(nullptr, DDP_EINVAL, "ddp_set_schedule: ctx is NULL");
-    if (!ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_set_schedule: no model registered");
-    if (H < 1 || !set_ptr || !set_layers) return fail(ctx, DDP_EINVAL, "ddp_set_schedule: bad argument");
-    if (set_ptr[0] != 0) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: set_ptr[0] must be 0");
-    int rc = check_device(ctx, "ddp_set_schedule");
-    if (rc != DDP_OK) return rc;
-    for (int s = 0; s < H; ++s) {
-        if (set_ptr[s + 1] < set_ptr[s]) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: set_ptr is not monotone");
-        std::vector<char> seen((size_t)ctx->L, 0);
-        for (int j = set_ptr[s]; j < set_ptr[s + 1]; ++j) {
-            int l = set_layers[j];
-            if (l < 0 || l >= ctx->L) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: layer id out of range in slot " + std::to_string(s));
-            if (seen[(size_t)l]) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: layer " + std::to_string(l) + " listed twice in slot " + std::to_string(s));
-            seen[(size_t)l] = 1;
+    try {
+        if (!ctx) return fail(nullptr, DDP_EINVAL, "ddp_set_schedule: ctx is NULL");
+        if (!ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_set_schedule: no model registered");
+        if (H < 1 || !set_ptr || !set_layers) return fail(ctx, DDP_EINVAL, "ddp_set_schedule: bad argument");
+        if (set_ptr[0] != 0) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: set_ptr[0] must be 0");
+        int rc = check_device(ctx, "ddp_set_schedule");
+        if (rc != DDP_OK) return rc;
+        for (int s = 0; s < H; ++s) {
+            if (set_ptr[s + 1] < set_ptr[s]) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: set_ptr is not monotone");
+            std::vector<char> seen((size_t)ctx->L, 0);
+            for (int j = set_ptr[s]; j < set_ptr[s + 1]; ++j) {
+                int l = set_layers[j];
+                if (l < 0 || l >= ctx->L) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: layer id out of range in slot " + std::to_string(s));
+                if (seen[(size_t)l]) return fail(ctx, DDP_ESCHED, "ddp_set_schedule: layer " + std::to_string(l) + " listed twice in slot " + std::to_string(s));
+                seen[(size_t)l] = 1;
+            }
         }
-    }
 
-    drop_schedule(ctx);
-    std::vector<SlotTables> slots((size_t)H);
-    int64_t max_mean_chunks = 0;
-    for (int s = 0; s < H; ++s) {
-        SlotTables &st = slots[(size_t)s];
-        std::vector<CopyChunk> cc;
-        std::vector<MeanChunk> mc;
-        std::vector<int32_t> lcp, fused_ranges;
-        std::vector<int64_t> tflat((size_t)ctx->T, -1);
-        int64_t off = 0;
-        for (int j = set_ptr[s]; j < set_ptr[s + 1]; ++j) {
-            const int l = set_layers[j];
-            st.layers.push_back(l);
+        drop_schedule(ctx);
+        std::vector<SlotTables> slots((size_t)H);
+        int64_t max_mean_chunks = 0;
+        for (int s = 0; s < H; ++s) {
+            SlotTables &st = slots[(size_t)s];
+            std::vector<CopyChunk> cc;
+            std::vector<MeanChunk> mc;
+            std::vector<int32_t> lcp, fused_ranges;
+            std::vector<int64_t> tflat((size_t)ctx->T, -1);
+            int64_t off = 0;
+            for (int j = set_ptr[s]; j < set_ptr[s + 1]; ++j) {
+                const int l = set_layers[j];
+                st.layers.push_back(l);
+                st.layer_begin.push_back(off);
+                lcp.push_back((int32_t)mc.size());
+                fused_ranges.push_back(ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)l]]);
+                fused_ranges.push_back(ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)l + 1]]);
+                const int64_t layer_start = off;
+                for (int t = ctx->layer_first_tensor[(size_t)l]; t < ctx->layer_first_tensor[(size_t)l + 1]; ++t) {
+                    st.tensors.push_back(t);
+                    st.tensor_off.push_back(off);
+                    tflat[(size_t)t] = off;
+                    for (int64_t b = 0; b < ctx->numel[(size_t)t]; b += ctx->copy_chunk) {
+                        int64_t n = std::min<int64_t>(ctx->copy_chunk, ctx->numel[(size_t)t] - b);
+                        cc.push_back({b, off + b, t, (int32_t)n});
+                    }
+                    off += ctx->numel[(size_t)t];
+                }
+                // mean chunks: cut the layer's flat range at multiples of mean_chunk measured from a 4-element
+                // boundary, so that every chunk but the first starts 16-byte aligned
+                int64_t b = layer_start;
+                while (b < off) {
+                    int64_t e = std::min<int64_t>(off, (b / 4) * 4 + ctx->mean_chunk);
+                    mc.push_back({b, (int32_t)(e - b), (int32_t)mc.size()});
+                    b = e;
+                }
+            }
             st.layer_begin.push_back(off);
             lcp.push_back((int32_t)mc.size());
-            fused_ranges.push_back(ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)l]]);
-            fused_ranges.push_back(ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)l + 1]]);
-            const int64_t layer_start = off;
-            for (int t = ctx->layer_first_tensor[(size_t)l]; t < ctx->layer_first_tensor[(size_t)l + 1]; ++t) {
-                st.tensors.push_back(t);
-                st.tensor_off.push_back(off);
-                tflat[(size_t)t] = off;
-                for (int64_t b = 0; b < ctx->numel[(size_t)t]; b += ctx->copy_chunk) {
-                    int64_t n = std::min<int64_t>(ctx->copy_chunk, ctx->numel[(size_t)t] - b);
-                    cc.push_back({b, off + b, t, (int32_t)n});
-                }
-                off += ctx->numel[(size_t)t];
+            if (mc.size() > (size_t)0x7fffffff || cc.size() > (size_t)0x7fffffff) {
+                for (auto &x : slots) free_slot(x);
+                return fail(ctx, DDP_ESHAPE, "ddp_set_schedule: more than 2^31-1 chunks in a slot; raise mean_chunk / copy_chunk");
             }
-            // mean chunks: cut the layer's flat range at multiples of mean_chunk measured from a 4-element
-            // boundary, so that every chunk but the first starts 16-byte aligned
-            int64_t b = layer_start;
-            while (b < off) {
-                int64_t e = std::min<int64_t>(off, (b / 4) * 4 + ctx->mean_chunk);
-                mc.push_back({b, (int32_t)(e - b), (int32_t)mc.size()});
-                b = e;
+            st.numel = off;
+            st.n_copy = (int64_t)cc.size();
+            st.n_mean = (int64_t)mc.size();
+            max_mean_chunks = std::max(max_mean_chunks, st.n_mean);
+            interleave_segments(cc, ctx->dispatch_ways);
+            interleave_segments(mc, ctx->dispatch_ways);
+            rc = upload(ctx, cc, &st.d_copy);
+            if (rc == DDP_OK) rc = upload(ctx, mc, &st.d_mean);
+            std::vector<int32_t> mean_ranges;
+            for (size_t i = 0; i + 1 < lcp.size(); ++i) {
+                mean_ranges.push_back(lcp[i]);
+                mean_ranges.push_back(lcp[i + 1]);
+            }
+            if (rc == DDP_OK) rc = upload(ctx, mean_ranges, &st.d_layer_ranges);
+            if (rc == DDP_OK) rc = upload(ctx, tflat, &st.d_tensor_flat_off);
+            if (rc == DDP_OK) rc = upload(ctx, fused_ranges, &st.d_fused_ranges);
+            if (rc != DDP_OK) {
+                for (auto &x : slots) free_slot(x);
+                return rc;
             }
         }
-        st.layer_begin.push_back(off);
-        lcp.push_back((int32_t)mc.size());
-        st.numel = off;
-        st.n_copy = (int64_t)cc.size();
-        st.n_mean = (int64_t)mc.size();
-        max_mean_chunks = std::max(max_mean_chunks, st.n_mean);
-        interleave_segments(cc, ctx->dispatch_ways);
-        interleave_segments(mc, ctx->dispatch_ways);
-        rc = upload(ctx, cc, &st.d_copy);
-        if (rc == DDP_OK) rc = upload(ctx, mc, &st.d_mean);
-        std::vector<int32_t> mean_ranges;
-        for (size_t i = 0; i + 1 < lcp.size(); ++i) {
-            mean_ranges.push_back(lcp[i]);
-            mean_ranges.push_back(lcp[i + 1]);
+        max_mean_chunks = std::max(max_mean_chunks, ctx->n_update);  // the fused step keeps one partial per update chunk
+        if (max_mean_chunks > 0) {
+            hipError_t e = hipMalloc((void **)&ctx->d_partials, ((size_t)max_mean_chunks + (size_t)ctx->L * 64) * 2 * sizeof(double));
+            if (e != hipSuccess) {
+                ctx->d_partials = nullptr;
+                for (auto &x : slots) free_slot(x);
+                return fail(ctx, DDP_ENOMEM, std::string("ddp_set_schedule: hipMalloc of the reduction scratch failed: ") + hipGetErrorString(e));
+            }
+            ctx->partials_cap = max_mean_chunks;
+            ctx->d_slice_sums = ctx->d_partials + 2 * max_mean_chunks;
         }
-        if (rc == DDP_OK) rc = upload(ctx, mean_ranges, &st.d_layer_ranges);
-        if (rc == DDP_OK) rc = upload(ctx, tflat, &st.d_tensor_flat_off);
-        if (rc == DDP_OK) rc = upload(ctx, fused_ranges, &st.d_fused_ranges);
-        if (rc != DDP_OK) {
-            for (auto &x : slots) free_slot(x);
-            return rc;
-        }
+        ctx->slots = std::move(slots);
+        ctx->H = H;
+        return DDP_OK;
+    } catch (const std::exception &e) {
+        return fail(ctx, DDP_ENOMEM, std::string("ddp_set_schedule: host allocation failed: ") + e.what());
     }
-    max_mean_chunks = std::max(max_mean_chunks, ctx->n_update);  // the fused step keeps one partial per update chunk
-    if (max_mean_chunks > 0) {
-        hipError_t e = hipMalloc((void **)&ctx->d_partials, ((size_t)max_mean_chunks + (size_t)ctx->L * 64) * 2 * sizeof(double));
-        if (e != hipSuccess) {
-            ctx->d_partials = nullptr;
-            for (auto &x : slots) free_slot(x);
-            return fail(ctx, DDP_ENOMEM, std::string("ddp_set_schedule: hipMalloc of the reduction scratch failed: ") + hipGetErrorString(e));
-        }
-        ctx->partials_cap = max_mean_chunks;
-        ctx->d_slice_sums = ctx->d_partials + 2 * max_mean_chunks;
-    }
-    ctx->slots = std::move(slots);
-    ctx->H = H;
-    return DDP_OK;
 }
 
 static const SlotTables *slot_of(const ddp_ctx *ctx, int slot, const char *who, int *rc) {

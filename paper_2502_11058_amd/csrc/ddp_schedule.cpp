@@ -10,6 +10,7 @@
 // Eq. (8) plus the `rem` inside its max always add up to one whole backward pass.
 #include <algorithm>
 #include <cstdint>
+#include <exception>
 #include <limits>
 #include <string>
 #include <vector>
@@ -160,87 +161,99 @@ void emit_cut(int L, int H, const std::vector<int> &cut, int32_t *out_slot, int3
 extern "C" int ddp_schedule(int policy, int L, int H, const int64_t *t_fp_ns, const int64_t *t_bp_ns,
                             const int64_t *t_comm_ns, int32_t *out_slot, int32_t *out_set_ptr, int32_t *out_set_layers,
                             int64_t *out_cost_ns) {
-    (void)t_fp_ns;  // R * t_FP is a constant of Eq. (7); it does not influence the partition
-    if (L < 1 || H < 1) return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule: L and H must be >= 1");
-    if (!out_slot || !out_set_ptr || !out_set_layers) return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule: NULL output");
-    if (policy < DDP_SCHED_ENP || policy > DDP_SCHED_ALG2) return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule: unknown policy");
-    const bool needs_times = policy == DDP_SCHED_OPT || policy == DDP_SCHED_ALG2;
-    if (needs_times && (!t_bp_ns || !t_comm_ns)) return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule: policy needs t_bp_ns and t_comm_ns");
-    Instance in;
-    const bool have_times = t_bp_ns && t_comm_ns;
-    if (have_times) {
-        int rc = make_instance(L, H, t_bp_ns, t_comm_ns, in);
-        if (rc != DDP_OK) return rc;
-    }
-    if (out_cost_ns) *out_cost_ns = -1;
-
-    if (policy == DDP_SCHED_ROUND_ROBIN) {
-        int n = 0;
-        for (int s = 0; s < H; ++s) {
-            out_set_ptr[s] = n;
-            for (int l = L - 1; l >= 0; --l)
-                if (l % H == s) {
-                    out_set_layers[n++] = l;
-                    out_slot[l] = s;
-                }
+    try {
+        (void)t_fp_ns;  // R * t_FP is a constant of Eq. (7); it does not influence the partition
+        if (L < 1 || H < 1) return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule: L and H must be >= 1");
+        if (!out_slot || !out_set_ptr || !out_set_layers) return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule: NULL output");
+        if (policy < DDP_SCHED_ENP || policy > DDP_SCHED_ALG2) return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule: unknown policy");
+        const bool needs_times = policy == DDP_SCHED_OPT || policy == DDP_SCHED_ALG2;
+        if (needs_times && (!t_bp_ns || !t_comm_ns)) return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule: policy needs t_bp_ns and t_comm_ns");
+        Instance in;
+        const bool have_times = t_bp_ns && t_comm_ns;
+        if (have_times) {
+            int rc = make_instance(L, H, t_bp_ns, t_comm_ns, in);
+            if (rc != DDP_OK) return rc;
         }
-        out_set_ptr[H] = n;
-        return DDP_OK;
-    }
-    if (policy == DDP_SCHED_EVERY) {
-        int n = 0;
-        for (int s = 0; s < H; ++s) {
-            out_set_ptr[s] = n;
-            for (int l = L - 1; l >= 0; --l) out_set_layers[n++] = l;
-        }
-        out_set_ptr[H] = n;
-        for (int l = 0; l < L; ++l) out_slot[l] = 0;
-        return DDP_OK;
-    }
+        if (out_cost_ns) *out_cost_ns = -1;
 
-    std::vector<int> cut(H + 1, 0);
-    if (policy == DDP_SCHED_ENP) {
-        for (int h = 0; h < H; ++h) cut[h + 1] = cut[h] + L / H + (h < L % H ? 1 : 0);
-    } else if (policy == DDP_SCHED_FULL) {
-        cut[H] = L;  // sets 0..H-2 empty, the last one holds everything: synchronise when (r+1) % H == 0
-    } else if (policy == DDP_SCHED_OPT) {
-        cut = solve_opt(in);
-    } else {
-        cut = solve_alg2(in).best;
+        if (policy == DDP_SCHED_ROUND_ROBIN) {
+            int n = 0;
+            for (int s = 0; s < H; ++s) {
+                out_set_ptr[s] = n;
+                for (int l = L - 1; l >= 0; --l)
+                    if (l % H == s) {
+                        out_set_layers[n++] = l;
+                        out_slot[l] = s;
+                    }
+            }
+            out_set_ptr[H] = n;
+            return DDP_OK;
+        }
+        if (policy == DDP_SCHED_EVERY) {
+            int n = 0;
+            for (int s = 0; s < H; ++s) {
+                out_set_ptr[s] = n;
+                for (int l = L - 1; l >= 0; --l) out_set_layers[n++] = l;
+            }
+            out_set_ptr[H] = n;
+            for (int l = 0; l < L; ++l) out_slot[l] = 0;
+            return DDP_OK;
+        }
+
+        std::vector<int> cut(H + 1, 0);
+        if (policy == DDP_SCHED_ENP) {
+            for (int h = 0; h < H; ++h) cut[h + 1] = cut[h] + L / H + (h < L % H ? 1 : 0);
+        } else if (policy == DDP_SCHED_FULL) {
+            cut[H] = L;  // sets 0..H-2 empty, the last one holds everything: synchronise when (r+1) % H == 0
+        } else if (policy == DDP_SCHED_OPT) {
+            cut = solve_opt(in);
+        } else {
+            cut = solve_alg2(in).best;
+        }
+        emit_cut(L, H, cut, out_slot, out_set_ptr, out_set_layers);
+        if (out_cost_ns && have_times) *out_cost_ns = cost_of_cuts(in, cut);
+        return DDP_OK;
+    } catch (const std::exception &e) {
+        return ddp::fail(nullptr, DDP_ENOMEM, std::string("ddp_schedule: host allocation failed: ") + e.what());
     }
-    emit_cut(L, H, cut, out_slot, out_set_ptr, out_set_layers);
-    if (out_cost_ns && have_times) *out_cost_ns = cost_of_cuts(in, cut);
-    return DDP_OK;
 }
 
 extern "C" int ddp_schedule_cost(int L, int H, const int64_t *t_bp_ns, const int64_t *t_comm_ns, const int32_t *set_ptr,
                                  const int32_t *set_layers, int64_t *out_cost_ns) {
-    if (L < 1 || H < 1 || !t_bp_ns || !t_comm_ns || !set_ptr || !set_layers || !out_cost_ns)
-        return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_cost: bad argument");
-    Instance in;
-    int rc = make_instance(L, H, t_bp_ns, t_comm_ns, in);
-    if (rc != DDP_OK) return rc;
-    if (set_ptr[0] != 0 || set_ptr[H] != L) return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_cost: sets must cover every layer once");
-    std::vector<int> cut(H + 1, 0);
-    for (int h = 0; h < H; ++h) {
-        if (set_ptr[h + 1] < set_ptr[h]) return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_cost: set_ptr not monotone");
-        cut[h + 1] = set_ptr[h + 1];
+    try {
+        if (L < 1 || H < 1 || !t_bp_ns || !t_comm_ns || !set_ptr || !set_layers || !out_cost_ns)
+            return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_cost: bad argument");
+        Instance in;
+        int rc = make_instance(L, H, t_bp_ns, t_comm_ns, in);
+        if (rc != DDP_OK) return rc;
+        if (set_ptr[0] != 0 || set_ptr[H] != L) return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_cost: sets must cover every layer once");
+        std::vector<int> cut(H + 1, 0);
+        for (int h = 0; h < H; ++h) {
+            if (set_ptr[h + 1] < set_ptr[h]) return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_cost: set_ptr not monotone");
+            cut[h + 1] = set_ptr[h + 1];
+        }
+        for (int j = 0; j < L; ++j)
+            if (set_layers[j] != L - 1 - j)
+                return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_cost: sets are not a cut of the BP-ordered layer sequence");
+        *out_cost_ns = cost_of_cuts(in, cut);
+        return DDP_OK;
+    } catch (const std::exception &e) {
+        return ddp::fail(nullptr, DDP_ENOMEM, std::string("ddp_schedule_cost: host allocation failed: ") + e.what());
     }
-    for (int j = 0; j < L; ++j)
-        if (set_layers[j] != L - 1 - j)
-            return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_cost: sets are not a cut of the BP-ordered layer sequence");
-    *out_cost_ns = cost_of_cuts(in, cut);
-    return DDP_OK;
 }
 
 extern "C" int ddp_schedule_alg2_solutions(int L, int H, const int64_t *t_bp_ns, const int64_t *t_comm_ns, int64_t *out_count) {
-    if (L < 1 || H < 1 || !t_bp_ns || !t_comm_ns || !out_count)
-        return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_alg2_solutions: bad argument");
-    Instance in;
-    int rc = make_instance(L, H, t_bp_ns, t_comm_ns, in);
-    if (rc != DDP_OK) return rc;
-    *out_count = solve_alg2(in).n_solutions;
-    return DDP_OK;
+    try {
+        if (L < 1 || H < 1 || !t_bp_ns || !t_comm_ns || !out_count)
+            return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_alg2_solutions: bad argument");
+        Instance in;
+        int rc = make_instance(L, H, t_bp_ns, t_comm_ns, in);
+        if (rc != DDP_OK) return rc;
+        *out_count = solve_alg2(in).n_solutions;
+        return DDP_OK;
+    } catch (const std::exception &e) {
+        return ddp::fail(nullptr, DDP_ENOMEM, std::string("ddp_schedule_alg2_solutions: host allocation failed: ") + e.what());
+    }
 }
 
 // Reads a CSR schedule that must be a cut of the BP-ordered layer sequence; fills cut[0..H].
@@ -262,31 +275,35 @@ static int read_cut(const char *who, int L, int H, const int32_t *set_ptr, const
 // max(rem, own communication), i.e. within the backward work that hides it (or not at all if it already overflows).
 extern "C" int ddp_schedule_fill_bubbles(int L, int H, const int64_t *t_bp_ns, const int64_t *t_comm_ns, const int32_t *set_ptr,
                                          const int32_t *set_layers, int32_t *out_set_ptr, int32_t *out_set_layers, int32_t *out_extra) {
-    if (L < 1 || H < 1 || !t_bp_ns || !t_comm_ns || !set_ptr || !set_layers || !out_set_ptr || !out_set_layers)
-        return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_fill_bubbles: bad argument");
-    Instance in;
-    int rc = make_instance(L, H, t_bp_ns, t_comm_ns, in);
-    if (rc != DDP_OK) return rc;
-    std::vector<int> cut;
-    rc = read_cut("ddp_schedule_fill_bubbles", L, H, set_ptr, set_layers, cut);
-    if (rc != DDP_OK) return rc;
-    int n = 0;
-    for (int h = 0; h < H; ++h) {
-        const int a = cut[h], b = cut[h + 1];
-        const bool empty = a == b;
-        const int64_t rem = in.rem(empty ? 0 : a);  // an empty set would start with the top layer
-        const int64_t own = in.PC[b] - in.PC[a];
-        const int64_t budget = std::max(rem, own);
-        const int limit = empty ? L : a;  // stay disjoint from the set itself
-        int e = 0;
-        while (e < limit && own + in.PC[e + 1] <= budget) ++e;  // PC[e+1] = communication of the top e+1 layers
-        out_set_ptr[h] = n;
-        for (int j = 0; j < e; ++j) out_set_layers[n++] = L - 1 - j;
-        for (int j = a; j < b; ++j) out_set_layers[n++] = L - 1 - j;
-        if (out_extra) out_extra[h] = e;
+    try {
+        if (L < 1 || H < 1 || !t_bp_ns || !t_comm_ns || !set_ptr || !set_layers || !out_set_ptr || !out_set_layers)
+            return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_fill_bubbles: bad argument");
+        Instance in;
+        int rc = make_instance(L, H, t_bp_ns, t_comm_ns, in);
+        if (rc != DDP_OK) return rc;
+        std::vector<int> cut;
+        rc = read_cut("ddp_schedule_fill_bubbles", L, H, set_ptr, set_layers, cut);
+        if (rc != DDP_OK) return rc;
+        int n = 0;
+        for (int h = 0; h < H; ++h) {
+            const int a = cut[h], b = cut[h + 1];
+            const bool empty = a == b;
+            const int64_t rem = in.rem(empty ? 0 : a);  // an empty set would start with the top layer
+            const int64_t own = in.PC[b] - in.PC[a];
+            const int64_t budget = std::max(rem, own);
+            const int limit = empty ? L : a;  // stay disjoint from the set itself
+            int e = 0;
+            while (e < limit && own + in.PC[e + 1] <= budget) ++e;  // PC[e+1] = communication of the top e+1 layers
+            out_set_ptr[h] = n;
+            for (int j = 0; j < e; ++j) out_set_layers[n++] = L - 1 - j;
+            for (int j = a; j < b; ++j) out_set_layers[n++] = L - 1 - j;
+            if (out_extra) out_extra[h] = e;
+        }
+        out_set_ptr[H] = n;
+        return DDP_OK;
+    } catch (const std::exception &e) {
+        return ddp::fail(nullptr, DDP_ENOMEM, std::string("ddp_schedule_fill_bubbles: host allocation failed: ") + e.what());
     }
-    out_set_ptr[H] = n;
-    return DDP_OK;
 }
 
 // Eq. (7) on the time line of one iteration: layer l's backward is done at D(l) = sum of t_bp over layers >= l
@@ -296,39 +313,43 @@ extern "C" int ddp_schedule_fill_bubbles(int L, int H, const int64_t *t_bp_ns, c
 extern "C" int ddp_schedule_time_model(int L, int H, const int64_t *t_fp_ns, const int64_t *t_bp_ns, const int64_t *t_comm_ns,
                                        const int32_t *set_ptr, const int32_t *set_layers, int64_t *out_iter_ns,
                                        int64_t *out_exposed_ns, int64_t *out_period_ns) {
-    if (L < 1 || H < 1 || !t_bp_ns || !t_comm_ns || !set_ptr || !set_layers || !out_iter_ns)
-        return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_time_model: bad argument");
-    Instance in;
-    int rc = make_instance(L, H, t_bp_ns, t_comm_ns, in);
-    if (rc != DDP_OK) return rc;
-    __int128 fp_total = 0;
-    if (t_fp_ns)
-        for (int l = 0; l < L; ++l) {
-            if (t_fp_ns[l] < 0) return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_time_model: negative forward time");
-            fp_total += t_fp_ns[l];
+    try {
+        if (L < 1 || H < 1 || !t_bp_ns || !t_comm_ns || !set_ptr || !set_layers || !out_iter_ns)
+            return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_time_model: bad argument");
+        Instance in;
+        int rc = make_instance(L, H, t_bp_ns, t_comm_ns, in);
+        if (rc != DDP_OK) return rc;
+        __int128 fp_total = 0;
+        if (t_fp_ns)
+            for (int l = 0; l < L; ++l) {
+                if (t_fp_ns[l] < 0) return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_time_model: negative forward time");
+                fp_total += t_fp_ns[l];
+            }
+        if (set_ptr[0] != 0) return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_time_model: set_ptr[0] must be 0");
+        __int128 period = 0;
+        for (int h = 0; h < H; ++h) {
+            if (set_ptr[h + 1] < set_ptr[h]) return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_time_model: set_ptr not monotone");
+            __int128 comm_end = 0;
+            int prev = L;
+            for (int j = set_ptr[h]; j < set_ptr[h + 1]; ++j) {
+                const int l = set_layers[j];
+                if (l < 0 || l >= L || l >= prev)
+                    return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_time_model: a set must list distinct layers in BP order (descending)");
+                prev = l;
+                const __int128 done = in.PB[L - l];
+                comm_end = std::max(done, comm_end) + t_comm_ns[l];
+            }
+            const __int128 bp_end = in.PB[L];
+            const __int128 end = std::max(bp_end, comm_end) + fp_total;
+            if (end > (__int128)std::numeric_limits<int64_t>::max() || period + end > (__int128)std::numeric_limits<int64_t>::max())
+                return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_time_model: times overflow int64 nanoseconds");
+            out_iter_ns[h] = (int64_t)end;
+            if (out_exposed_ns) out_exposed_ns[h] = (int64_t)(comm_end > bp_end ? comm_end - bp_end : 0);
+            period += end;
         }
-    if (set_ptr[0] != 0) return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_time_model: set_ptr[0] must be 0");
-    __int128 period = 0;
-    for (int h = 0; h < H; ++h) {
-        if (set_ptr[h + 1] < set_ptr[h]) return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_time_model: set_ptr not monotone");
-        __int128 comm_end = 0;
-        int prev = L;
-        for (int j = set_ptr[h]; j < set_ptr[h + 1]; ++j) {
-            const int l = set_layers[j];
-            if (l < 0 || l >= L || l >= prev)
-                return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_time_model: a set must list distinct layers in BP order (descending)");
-            prev = l;
-            const __int128 done = in.PB[L - l];
-            comm_end = std::max(done, comm_end) + t_comm_ns[l];
-        }
-        const __int128 bp_end = in.PB[L];
-        const __int128 end = std::max(bp_end, comm_end) + fp_total;
-        if (end > (__int128)std::numeric_limits<int64_t>::max() || period + end > (__int128)std::numeric_limits<int64_t>::max())
-            return ddp::fail(nullptr, DDP_EINVAL, "ddp_schedule_time_model: times overflow int64 nanoseconds");
-        out_iter_ns[h] = (int64_t)end;
-        if (out_exposed_ns) out_exposed_ns[h] = (int64_t)(comm_end > bp_end ? comm_end - bp_end : 0);
-        period += end;
+        if (out_period_ns) *out_period_ns = (int64_t)period;
+        return DDP_OK;
+    } catch (const std::exception &e) {
+        return ddp::fail(nullptr, DDP_ENOMEM, std::string("ddp_schedule_time_model: host allocation failed: ") + e.what());
     }
-    if (out_period_ns) *out_period_ns = (int64_t)period;
-    return DDP_OK;
 }
