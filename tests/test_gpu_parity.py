@@ -275,6 +275,17 @@ def test_fused_odd_shapes(oracle, arena_offset):
     run_trajectory(oracle, w, fused=True, arena_offset=arena_offset, policy="full")
 
 
+@pytest.mark.parametrize("options", [
+    {"dispatch_ways": 8}, {"dispatch_ways": 3, "update_chunk": 1024, "mean_chunk": 2048, "copy_chunk": 4096},
+    {"update_lds": 0, "mean_lds": 0, "copy_lds": 0, "nontemporal": 0}, {"update_chunk": 1048576, "mean_chunk": 1048576, "copy_chunk": 1048576},
+])
+def test_launch_options_do_not_change_results(oracle, options):
+    t = run_trajectory(oracle, W.odd(n_replicas=8), options=options, arena_offset=2)
+    assert t.frac() == 1.0
+    t = run_trajectory(oracle, W.small_llama(), options=options, fused=True, iters=4)
+    assert t.frac() == 1.0
+
+
 def test_single_replica_is_identity(oracle):
     w = W.tiny()
     w.n_replicas = 1
