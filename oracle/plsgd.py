@@ -139,6 +139,34 @@ def layer_stats(replicas: Sequence[np.ndarray], mean_: np.ndarray, begin: int, e
     return g.value, m.value
 
 
+def pack_wire16(tensors: Sequence[np.ndarray], off: Sequence[int], total: int) -> np.ndarray:
+    flat = np.zeros(total, dtype=np.uint16)
+    ts = [_chk(t, np.float32) for t in tensors]
+    ne = np.asarray([t.size for t in ts], dtype=np.int64)
+    of = np.asarray(off, dtype=np.int64)
+    lib().orc_pack_wire16(len(ts), _ptr_array(ts), _p(ne), _p(of), _p(flat))
+    return flat
+
+
+def mean_wire16(replicas: Sequence[np.ndarray]) -> np.ndarray:
+    """Average of N flat bf16 buffers (bit patterns, uint16) in rank order; fp32 result."""
+    xs = [_chk(x, np.uint16) for x in replicas]
+    n = xs[0].size
+    assert all(x.size == n for x in xs)
+    out = np.empty(n, dtype=np.float32)
+    lib().orc_mean_wire16(len(xs), _ptr_array(xs), C.c_int64(n), _p(out))
+    return out
+
+
+def layer_stats_wire16(replicas: Sequence[np.ndarray], mean_: np.ndarray, begin: int, end: int) -> Tuple[float, float]:
+    xs = [_chk(x, np.uint16) for x in replicas]
+    g = C.c_double(0.0)
+    m = C.c_double(0.0)
+    lib().orc_layer_stats_wire16(len(xs), _ptr_array(xs), _p(_chk(mean_, np.float32)), C.c_int64(begin), C.c_int64(end),
+                                 C.byref(g), C.byref(m))
+    return g.value, m.value
+
+
 def sgdm(p: np.ndarray, g: np.ndarray, buf: np.ndarray, lr: float, mu: float) -> None:
     """In place on p and buf."""
     assert p.size == g.size == buf.size
@@ -298,9 +326,10 @@ class Worker:
         self.s1 = [np.zeros_like(x) for x in self.p] if optimizer == "adamw" else None
         self.model = [bf16_rne(x) for x in self.p] if bf16_model else None
 
-    def pack_slot(self, set_layers: Sequence[int]):
+    def pack_slot(self, set_layers: Sequence[int], wire16: bool = False):
         off, order, total = slot_offsets(self.layer_of, self.numel, set_layers)
-        flat = pack([self.p[t] for t in order], [off[t] for t in order], total)
+        fn = pack_wire16 if wire16 else pack
+        flat = fn([self.p[t] for t in order], [off[t] for t in order], total)
         return flat, off, order, total
 
     def unpack_slot(self, flat: np.ndarray, off, order) -> None:
@@ -330,13 +359,14 @@ class Worker:
                 out.append((0, 0))
         return out
 
-    def sync(self, set_layers: Sequence[int], peers: Sequence[np.ndarray], local_rank: int):
+    def sync(self, set_layers: Sequence[int], peers: Sequence[np.ndarray], local_rank: int, wire16: bool = False):
         """pack -> average with the peers (rank order, local buffer at position local_rank) -> unpack.
-        Returns (flat mean, [(Gamma^l, ||mean^l||^2) per scheduled layer])."""
-        flat, off, order, total = self.pack_slot(set_layers)
+        Returns (flat mean, [(Gamma^l, ||mean^l||^2) per scheduled layer]).  wire16: bf16 buffers on the wire."""
+        flat, off, order, total = self.pack_slot(set_layers, wire16)
         reps = list(peers[:local_rank]) + [flat] + list(peers[local_rank:])
-        out = mean(reps)
-        stats = [layer_stats(reps, out, b, e) for (b, e) in self.layer_ranges(set_layers, off, order)]
+        out = (mean_wire16 if wire16 else mean)(reps)
+        st = layer_stats_wire16 if wire16 else layer_stats
+        stats = [st(reps, out, b, e) for (b, e) in self.layer_ranges(set_layers, off, order)]
         self.unpack_slot(out, off, order)
         return out, stats
 

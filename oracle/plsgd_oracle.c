@@ -137,6 +137,43 @@ void orc_layer_stats(int N, const float *const *x, const float *mean, int64_t be
 }
 
 /* ------------------------------------------------------------------------------------------------------ */
+/* bf16 on the wire (an option of this build, not of the paper, which does not discuss precision)           */
+/* ------------------------------------------------------------------------------------------------------ */
+
+/* Reading: what travels is bf16_rne of each replica's fp32 value, the local replica's included, so that every
+ * worker averages the same N numbers and all replicas still agree bit for bit after a synchronisation.  The sum
+ * runs over the widened values in fp32, rank order, then one multiply by 1.0f/N; the result is kept in fp32. */
+void orc_pack_wire16(int n, const float *const *src, const int64_t *numel, const int64_t *off, uint16_t *flat) {
+    for (int t = 0; t < n; ++t)
+        for (int64_t i = 0; i < numel[t]; ++i) flat[off[t] + i] = bf16_rne_one(src[t][i]);
+}
+
+void orc_mean_wire16(int N, const uint16_t *const *x, int64_t n, float *out) {
+    const float inv_n = 1.0f / (float)N;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        float acc = bf16_widen_one(x[0][i]);
+        for (int k = 1; k < N; ++k) acc = acc + bf16_widen_one(x[k][i]);
+        out[i] = acc * inv_n;
+    }
+}
+
+/* Divergence and norm as in orc_layer_stats, measured against the values that were actually averaged. */
+void orc_layer_stats_wire16(int N, const uint16_t *const *x, const float *mean, int64_t begin, int64_t end, double *gamma,
+                            double *msq) {
+    long double g = 0.0L, m = 0.0L;
+    for (int64_t i = begin; i < end; ++i) {
+        for (int k = 0; k < N; ++k) {
+            float d = mean[i] - bf16_widen_one(x[k][i]);
+            g += (long double)((double)d * (double)d);
+        }
+        m += (long double)((double)mean[i] * (double)mean[i]);
+    }
+    *gamma = (double)(g / (long double)N);
+    *msq = (double)m;
+}
+
+/* ------------------------------------------------------------------------------------------------------ */
 /* Eq. (5), first case: the local update (Algorithm 1, "update model"), with the optimizers of Sec. 5.1     */
 /* ------------------------------------------------------------------------------------------------------ */
 
