@@ -206,6 +206,25 @@ int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream);
 int ddp_fused_sync_update(ddp_ctx *ctx, int slot, const float *const *peers, int N, int local_rank, double *layer_stats,
                           const ddp_opt *opt, void *stream);
 
+/* bf16 on the wire (an option of this library, not a step of the paper: the paper leaves the precision of the
+ * exchanged parameters open, and its cost model, Sec. 3.1 / Eq. (7), charges communication per byte, so halving
+ * the bytes of a layer halves its t_comm).  Reading taken here: every replica, the local one included, contributes
+ * bf16_rne of its fp32 value, so that all workers average the same N buffers and stay bit-identical after a
+ * synchronisation (Algorithm 1's invariant); the sum is still fp32 in rank order, times fp32(1/N), and the result is
+ * an fp32 buffer.  Buffers named *16 hold bf16 bit patterns (2 bytes per element), device memory, 16-byte aligned,
+ * ddp_slot_numel(slot) elements, same flat layout as ddp_pack.
+ *
+ * ddp_pack_wire16:            flat_local16[off_t + i] = bf16_rne(sync_t[i])
+ * ddp_partial_average_wire16: flat_out[j] = ( sum_{k in rank order} widen(x16_k[j]) ) * fp32(1/N); statistics as in
+ *                             ddp_partial_average with x_k = widen(x16_k).  flat_out (fp32) must not overlap any input.
+ * ddp_fused_sync_update_wire16: as ddp_fused_sync_update with bf16 peer buffers; bit-identical to
+ *                             ddp_pack_wire16 -> ddp_partial_average_wire16 -> ddp_unpack -> ddp_local_update. */
+int ddp_pack_wire16(ddp_ctx *ctx, int slot, uint16_t *flat_local16, void *stream);
+int ddp_partial_average_wire16(ddp_ctx *ctx, int slot, const uint16_t *flat_local16, const uint16_t *const *peers16, int N,
+                               int local_rank, float *flat_out, double *layer_stats, void *stream);
+int ddp_fused_sync_update_wire16(ddp_ctx *ctx, int slot, const uint16_t *const *peers16, int N, int local_rank,
+                                 double *layer_stats, const ddp_opt *opt, void *stream);
+
 /* Message of the last failure on this context (ctx == NULL: last failure of ddp_create / ddp_schedule* in
  * this thread).  Never NULL; valid until the next call on the same context / thread. */
 const char *ddp_last_error(const ddp_ctx *ctx);

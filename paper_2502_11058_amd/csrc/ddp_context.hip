@@ -435,26 +435,30 @@ extern "C" int ddp_unpack(ddp_ctx *ctx, int slot, const float *flat, void *strea
     return after_launch(ctx, "ddp_unpack", rc);
 }
 
-extern "C" int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_local, const float *const *peers, int N,
-                                   int local_rank, float *flat_out, double *layer_stats, void *stream) {
+// Shared body of the two averaging entry points; `who` names the caller in messages.  wire16: the replicas are
+// bf16 buffers (2 bytes per element) and the output is a separate fp32 buffer.
+static int partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, const void *flat_local, const void *const *peers,
+                                int N, int local_rank, float *flat_out, double *layer_stats, void *stream) {
     int rc;
-    const SlotTables *s = slot_of(ctx, slot, "ddp_partial_average", &rc);
+    const std::string w(who);
+    const SlotTables *s = slot_of(ctx, slot, who, &rc);
     if (!s) return rc;
-    if ((rc = check_device(ctx, "ddp_partial_average")) != DDP_OK) return rc;
-    if (N < 1 || N > DDP_MAX_REPLICAS) return fail(ctx, DDP_EINVAL, "ddp_partial_average: N must be in [1, " + std::to_string((int)DDP_MAX_REPLICAS) + "]");
-    if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, "ddp_partial_average: local_rank out of range");
-    if (N > 1 && !peers) return fail(ctx, DDP_EINVAL, "ddp_partial_average: peers is NULL");
+    if ((rc = check_device(ctx, who)) != DDP_OK) return rc;
+    if (N < 1 || N > DDP_MAX_REPLICAS) return fail(ctx, DDP_EINVAL, w + ": N must be in [1, " + std::to_string((int)DDP_MAX_REPLICAS) + "]");
+    if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, w + ": local_rank out of range");
+    if (N > 1 && !peers) return fail(ctx, DDP_EINVAL, w + ": peers is NULL");
     if (s->numel == 0) return DDP_OK;
-    if ((rc = check_flat(ctx, flat_local, "ddp_partial_average", "flat_local")) != DDP_OK) return rc;
-    if ((rc = check_flat(ctx, flat_out, "ddp_partial_average", "flat_out")) != DDP_OK) return rc;
-    if (layer_stats && !aligned(layer_stats, 8)) return fail(ctx, DDP_EALIGN, "ddp_partial_average: layer_stats must be 8-byte aligned");
-    const uintptr_t bytes = (uintptr_t)s->numel * 4;
-    auto overlaps = [&](const void *a, const void *b) {
-        uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
-        return x < y + bytes && y < x + bytes;
+    if ((rc = check_flat(ctx, flat_local, who, "flat_local")) != DDP_OK) return rc;
+    if ((rc = check_flat(ctx, flat_out, who, "flat_out")) != DDP_OK) return rc;
+    if (layer_stats && !aligned(layer_stats, 8)) return fail(ctx, DDP_EALIGN, w + ": layer_stats must be 8-byte aligned");
+    const uintptr_t out_bytes = (uintptr_t)s->numel * 4, in_bytes = (uintptr_t)s->numel * (wire16 ? 2 : 4);
+    auto overlaps_out = [&](const void *in) {
+        uintptr_t x = (uintptr_t)in, y = (uintptr_t)flat_out;
+        return x < y + out_bytes && y < x + in_bytes;
     };
-    if (flat_out != flat_local && overlaps(flat_out, flat_local))
-        return fail(ctx, DDP_EINVAL, "ddp_partial_average: flat_out partially overlaps flat_local");
+    // fp32: exactly in place is fine (each element is read before it is written by the same thread)
+    if (!(flat_out == flat_local && !wire16) && overlaps_out(flat_local))
+        return fail(ctx, DDP_EINVAL, w + (wire16 ? ": flat_out overlaps flat_local" : ": flat_out partially overlaps flat_local"));
     MeanLaunch a{};
     int p = 0;
     for (int k = 0; k < N; ++k) {
@@ -462,11 +466,12 @@ extern "C" int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_loc
             a.x[k] = flat_local;
             continue;
         }
-        const float *q = peers[p++];
-        if ((rc = check_flat(ctx, q, "ddp_partial_average", "a peer buffer")) != DDP_OK) return rc;
-        if (overlaps(q, flat_out)) return fail(ctx, DDP_EINVAL, "ddp_partial_average: a peer buffer overlaps flat_out");
+        const void *q = peers[p++];
+        if ((rc = check_flat(ctx, q, who, "a peer buffer")) != DDP_OK) return rc;
+        if (overlaps_out(q)) return fail(ctx, DDP_EINVAL, w + ": a peer buffer overlaps flat_out");
         a.x[k] = q;
     }
+    a.wire16 = wire16;
     a.n_replicas = N;
     a.inv_n = 1.0f / (float)N;
     a.out = flat_out;
@@ -480,7 +485,30 @@ extern "C" int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_loc
     a.nontemporal = ctx->nontemporal;
     a.lds_pad = ctx->mean_lds;
     rc = launch_mean(a, stream);
-    return after_launch(ctx, "ddp_partial_average", rc);
+    return after_launch(ctx, who, rc);
+}
+
+extern "C" int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_local, const float *const *peers, int N,
+                                   int local_rank, float *flat_out, double *layer_stats, void *stream) {
+    return partial_average_impl(ctx, "ddp_partial_average", false, slot, flat_local, reinterpret_cast<const void *const *>(peers), N,
+                                local_rank, flat_out, layer_stats, stream);
+}
+
+extern "C" int ddp_pack_wire16(ddp_ctx *ctx, int slot, uint16_t *flat_local16, void *stream) {
+    int rc;
+    const SlotTables *s = slot_of(ctx, slot, "ddp_pack_wire16", &rc);
+    if (!s) return rc;
+    if ((rc = check_device(ctx, "ddp_pack_wire16")) != DDP_OK) return rc;
+    if (s->numel == 0) return DDP_OK;
+    if ((rc = check_flat(ctx, flat_local16, "ddp_pack_wire16", "flat_local16")) != DDP_OK) return rc;
+    rc = launch_pack16(ctx->d_tensors, s->d_copy, s->n_copy, flat_local16, ctx->nontemporal, ctx->copy_lds, stream);
+    return after_launch(ctx, "ddp_pack_wire16", rc);
+}
+
+extern "C" int ddp_partial_average_wire16(ddp_ctx *ctx, int slot, const uint16_t *flat_local16, const uint16_t *const *peers16, int N,
+                                          int local_rank, float *flat_out, double *layer_stats, void *stream) {
+    return partial_average_impl(ctx, "ddp_partial_average_wire16", true, slot, flat_local16,
+                                reinterpret_cast<const void *const *>(peers16), N, local_rank, flat_out, layer_stats, stream);
 }
 
 static int make_scalars(ddp_ctx *ctx, const char *who, const ddp_opt *opt, UpdateScalars &s) {
@@ -522,26 +550,28 @@ extern "C" int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream) 
     return after_launch(ctx, "ddp_local_update", rc);
 }
 
-extern "C" int ddp_fused_sync_update(ddp_ctx *ctx, int slot, const float *const *peers, int N, int local_rank, double *layer_stats,
-                                     const ddp_opt *opt, void *stream) {
+static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, const void *const *peers, int N, int local_rank,
+                      double *layer_stats, const ddp_opt *opt, void *stream) {
     int rc;
-    const SlotTables *st = slot_of(ctx, slot, "ddp_fused_sync_update", &rc);
+    const std::string w(who);
+    const SlotTables *st = slot_of(ctx, slot, who, &rc);
     if (!st) return rc;
     UpdateScalars s{};
-    if ((rc = make_scalars(ctx, "ddp_fused_sync_update", opt, s)) != DDP_OK) return rc;
-    if ((rc = check_device(ctx, "ddp_fused_sync_update")) != DDP_OK) return rc;
-    if (N < 1 || N > DDP_MAX_REPLICAS) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update: N must be in [1, " + std::to_string((int)DDP_MAX_REPLICAS) + "]");
-    if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update: local_rank out of range");
-    if (N > 1 && !peers) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update: peers is NULL");
-    if (layer_stats && !aligned(layer_stats, 8)) return fail(ctx, DDP_EALIGN, "ddp_fused_sync_update: layer_stats must be 8-byte aligned");
+    if ((rc = make_scalars(ctx, who, opt, s)) != DDP_OK) return rc;
+    if ((rc = check_device(ctx, who)) != DDP_OK) return rc;
+    if (N < 1 || N > DDP_MAX_REPLICAS) return fail(ctx, DDP_EINVAL, w + ": N must be in [1, " + std::to_string((int)DDP_MAX_REPLICAS) + "]");
+    if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, w + ": local_rank out of range");
+    if (N > 1 && !peers) return fail(ctx, DDP_EINVAL, w + ": peers is NULL");
+    if (layer_stats && !aligned(layer_stats, 8)) return fail(ctx, DDP_EALIGN, w + ": layer_stats must be 8-byte aligned");
     FusedLaunch f{};
     int p = 0;
     for (int k = 0; k < N; ++k) {
         if (k == local_rank) continue;
-        const float *q = peers[p++];
-        if (st->numel > 0 && (rc = check_flat(ctx, q, "ddp_fused_sync_update", "a peer buffer")) != DDP_OK) return rc;
+        const void *q = peers[p++];
+        if (st->numel > 0 && (rc = check_flat(ctx, q, who, "a peer buffer")) != DDP_OK) return rc;
         f.x[k] = q;
     }
+    f.wire16 = wire16;
     f.n_replicas = N;
     f.local_rank = local_rank;
     f.inv_n = 1.0f / (float)N;
@@ -561,5 +591,17 @@ extern "C" int ddp_fused_sync_update(ddp_ctx *ctx, int slot, const float *const 
     f.n_layers = (int)st->layers.size();
     f.stats = layer_stats;
     f.lds_pad = ctx->update_lds;
-    return after_launch(ctx, "ddp_fused_sync_update", launch_fused(f, stream));
+    return after_launch(ctx, who, launch_fused(f, stream));
+}
+
+extern "C" int ddp_fused_sync_update(ddp_ctx *ctx, int slot, const float *const *peers, int N, int local_rank, double *layer_stats,
+                                     const ddp_opt *opt, void *stream) {
+    return fused_impl(ctx, "ddp_fused_sync_update", false, slot, reinterpret_cast<const void *const *>(peers), N, local_rank, layer_stats,
+                      opt, stream);
+}
+
+extern "C" int ddp_fused_sync_update_wire16(ddp_ctx *ctx, int slot, const uint16_t *const *peers16, int N, int local_rank,
+                                            double *layer_stats, const ddp_opt *opt, void *stream) {
+    return fused_impl(ctx, "ddp_fused_sync_update_wire16", true, slot, reinterpret_cast<const void *const *>(peers16), N, local_rank,
+                      layer_stats, opt, stream);
 }

@@ -66,7 +66,8 @@ struct SlotTables {
 
 // ---- launchers (ddp_kernels.hip) -------------------------------------------------------------------------------
 struct MeanLaunch {
-    const float *x[DDP_MAX_REPLICAS];  // replicas in rank order
+    const void *x[DDP_MAX_REPLICAS];  // replicas in rank order (fp32, or bf16 when wire16)
+    bool wire16;
     int n_replicas;
     float inv_n;
     float *out;
@@ -89,8 +90,11 @@ struct UpdateScalars {
 int launch_copy(bool unpack, const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, float *flat,
                 bool with_model, bool nontemporal, int lds_pad, void *stream);
 int launch_mean(const MeanLaunch &a, void *stream);
+int launch_pack16(const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, uint16_t *flat16, bool nontemporal, int lds_pad,
+                  void *stream);
 struct FusedLaunch {
-    const float *x[DDP_MAX_REPLICAS];  // peers in rank order (entry local_rank unused)
+    const void *x[DDP_MAX_REPLICAS];  // peers in rank order (entry local_rank unused); fp32, or bf16 when wire16
+    bool wire16;
     int n_replicas, local_rank;
     float inv_n;
     int kind, grad_dtype;

@@ -71,6 +71,27 @@ __device__ __forceinline__ u16x4 bf16_rne4(f32x4 v) {
     return r;
 }
 
+__device__ __forceinline__ f32x4 bf16_widen4(u16x4 h) {
+    return f32x4{bf16_widen(h.x), bf16_widen(h.y), bf16_widen(h.z), bf16_widen(h.w)};
+}
+
+// One replica's flat buffer as it arrives: fp32 (W16 = false) or bf16 bit patterns (W16 = true, widened exactly).
+// Element index i, or index v of a group of 4 elements (16 bytes of fp32, 8 bytes of bf16).
+template <bool W16>
+__device__ __forceinline__ float wire1(const void *base, int64_t i) {
+    if constexpr (W16)
+        return bf16_widen(reinterpret_cast<const unsigned short *>(base)[i]);
+    else
+        return reinterpret_cast<const float *>(base)[i];
+}
+template <bool W16, bool NT>
+__device__ __forceinline__ f32x4 wire4(const void *base, int64_t v) {
+    if constexpr (W16)
+        return bf16_widen4(ld<NT>(reinterpret_cast<const u16x4 *>(base) + v));
+    else
+        return ld<NT>(reinterpret_cast<const f32x4 *>(base) + v);
+}
+
 __device__ __forceinline__ int head_to_16B(const void *p, int n) {  // fp32 elements until p is 16-byte aligned
     int h = (int)((4u - (unsigned)((reinterpret_cast<uintptr_t>(p) >> 2) & 3u)) & 3u);
     return h < n ? h : n;
@@ -175,12 +196,41 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const TensorDesc *__rest
     }
 }
 
+// Pack for a bf16 wire: flat16[flat_begin + i] = bf16_rne(sync[t_begin + i]).  Stores are 8-byte aligned groups of
+// four; the source side uses the same two-granule window as copy_kernel when its alignment differs.
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void pack16_kernel(const TensorDesc *__restrict__ tensors, const CopyChunk *__restrict__ chunks,
+                                                          unsigned short *__restrict__ flat16) {
+    const CopyChunk ch = chunks[blockIdx.x];
+    const TensorDesc td = tensors[ch.tensor];
+    const float *src = td.sync + ch.t_begin;
+    unsigned short *dst = flat16 + ch.flat_begin;
+    const int n = ch.count;
+    const int tid = threadIdx.x;
+    int h = (int)((4 - (ch.flat_begin & 3)) & 3);  // the flat buffer is 16-byte aligned at element 0
+    if (h > n) h = n;
+    if (tid < h) dst[tid] = bf16_rne(src[tid]);
+    const int nv = (n - h) >> 2;
+    const int tail0 = h + 4 * nv;
+    if (tid < n - tail0) dst[tail0 + tid] = bf16_rne(src[tail0 + tid]);
+    if (nv == 0) return;
+    u16x4 *d4 = reinterpret_cast<u16x4 *>(dst + h);
+    const int delta = (int)((reinterpret_cast<uintptr_t>(src + h) >> 2) & 3u);
+    if (delta == 0) {
+        const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src + h);
+        for (int v = tid; v < nv; v += kThreads) st<NT>(d4 + v, bf16_rne4(ld<NT>(s4 + v)));
+    } else {
+        const f32x4 *s4 = reinterpret_cast<const f32x4 *>(src + h - delta);
+        for (int v = tid; v < nv; v += kThreads) st<NT>(d4 + v, bf16_rne4(window(s4[v], s4[v + 1], delta)));
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------------
 // partial average
 // ---------------------------------------------------------------------------------------------------------------
 
 struct MeanArgs {
-    const float *x[DDP_MAX_REPLICAS];
+    const void *x[DDP_MAX_REPLICAS];  // fp32 or bf16 flat buffers, rank order
     float *out;
     const MeanChunk *chunks;
     double *partials;
@@ -208,7 +258,7 @@ __device__ __forceinline__ double block_sum(double v, double *lds) {
 // Eq. (5), second case.  NREP > 0: replica count known at compile time (pointer loads and the sum fully
 // unrolled); NREP == 0: run-time count.  The sum runs left to right over replicas in rank order, in fp32, then
 // one multiply by 1/N.  STATS adds, per chunk, sum_k sum_i (out_i - x_k,i)^2 and sum_i out_i^2 in fp64.
-template <int NREP, bool STATS, bool NT>
+template <int NREP, bool STATS, bool NT, bool W16 = false>
 __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
     __shared__ double lds[2][kThreads / kWave];
     const MeanChunk ch = a.chunks[blockIdx.x];
@@ -220,12 +270,12 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
     double gsum = 0.0, msum = 0.0;
 
     auto one = [&](int64_t i) {
-        float acc = a.x[0][i];
-        for (int k = 1; k < nrep; ++k) acc = acc + a.x[k][i];
+        float acc = wire1<W16>(a.x[0], i);
+        for (int k = 1; k < nrep; ++k) acc = acc + wire1<W16>(a.x[k], i);
         const float m = acc * inv_n;
         if constexpr (STATS) {
             for (int k = 0; k < nrep; ++k) {
-                const float d = m - a.x[k][i];
+                const float d = m - wire1<W16>(a.x[k], i);
                 gsum += (double)d * (double)d;
             }
             msum += (double)m * (double)m;
@@ -266,7 +316,7 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
 #pragma unroll
             for (int b = 0; b < B; ++b)
 #pragma unroll
-                for (int k = 0; k < NREP; ++k) x[b][k] = ld<NT>(reinterpret_cast<const f32x4 *>(a.x[k]) + vbase + v + b * kThreads);
+                for (int k = 0; k < NREP; ++k) x[b][k] = wire4<W16, NT>(a.x[k], vbase + v + b * kThreads);
 #pragma unroll
             for (int b = 0; b < B; ++b) {
                 f32x4 acc = x[b][0];
@@ -284,7 +334,7 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
         for (; v < nv; v += kThreads) {
             f32x4 x[NREP];
 #pragma unroll
-            for (int k = 0; k < NREP; ++k) x[k] = ld<NT>(reinterpret_cast<const f32x4 *>(a.x[k]) + vbase + v);
+            for (int k = 0; k < NREP; ++k) x[k] = wire4<W16, NT>(a.x[k], vbase + v);
             f32x4 acc = x[0];
 #pragma unroll
             for (int k = 1; k < NREP; ++k) acc = acc + x[k];
@@ -298,11 +348,11 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
         }
     } else {
         for (int v = tid; v < nv; v += kThreads) {
-            f32x4 acc = ld<NT>(reinterpret_cast<const f32x4 *>(a.x[0]) + vbase + v);
-            for (int k = 1; k < nrep; ++k) acc = acc + ld<NT>(reinterpret_cast<const f32x4 *>(a.x[k]) + vbase + v);
+            f32x4 acc = wire4<W16, NT>(a.x[0], vbase + v);
+            for (int k = 1; k < nrep; ++k) acc = acc + wire4<W16, NT>(a.x[k], vbase + v);
             const f32x4 m = acc * inv_n;
             if constexpr (STATS) {
-                for (int k = 0; k < nrep; ++k) stats4(m, reinterpret_cast<const f32x4 *>(a.x[k])[vbase + v]);
+                for (int k = 0; k < nrep; ++k) stats4(m, wire4<W16, false>(a.x[k], vbase + v));
                 msq4(m);
             }
             st<NT>(o4 + v, m);
@@ -520,7 +570,7 @@ __global__ __launch_bounds__(kThreads) void update_kernel(const TensorDesc *__re
 // ---------------------------------------------------------------------------------------------------------------
 
 struct FusedArgs {
-    const float *x[DDP_MAX_REPLICAS];  // peers' flat buffers in rank order; entry local_rank is unused
+    const void *x[DDP_MAX_REPLICAS];  // peers' flat buffers (fp32 or bf16) in rank order; entry local_rank is unused
     const TensorDesc *tensors;
     const UpdateChunk *chunks;
     const int64_t *tensor_flat_off;     // per tensor: first flat index in this slot, or -1 if not scheduled
@@ -538,7 +588,7 @@ struct FusedArgs {
 // tensor's flat offset; same rank-ordered fp32 sum and 1/N multiply as mean_kernel), then updated; every other
 // chunk is updated only.  Result: the bits that pack -> partial average -> unpack -> local update produce, without
 // the flat round trips.  NREP > 0: replica count known at compile time; 0: run-time loop.
-template <bool ADAM, bool GBF16, bool MODEL, int NREP, bool STATS>
+template <bool ADAM, bool GBF16, bool MODEL, int NREP, bool STATS, bool W16 = false>
 __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
     typedef GradVec<GBF16> G;
     typedef typename G::elem gelem;
@@ -566,16 +616,20 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
     const float inv_n = a.inv_n;
     double gsum = 0.0, msum = 0.0;
 
-    // replica k's values for this chunk: the tensor itself for the local rank, else the peer's flat buffer
-    auto src = [&](int k) -> const float * { return k == lr ? p : a.x[k] + fo; };
+    // replica k's value at chunk element i / group of four v (after the head h): the tensor itself for the local rank
+    // (rounded to bf16 first if that is what the peers received from this worker), else the peer's flat buffer
+    auto rep1 = [&](int k, int i) -> float {
+        if (k == lr) return W16 ? bf16_widen(bf16_rne(p[i])) : p[i];
+        return wire1<W16>(a.x[k], fo + i);
+    };
 
     auto one = [&](int i) {
-        float acc = src(0)[i];
-        for (int k = 1; k < nrep; ++k) acc = acc + src(k)[i];
+        float acc = rep1(0, i);
+        for (int k = 1; k < nrep; ++k) acc = acc + rep1(k, i);
         const float m = acc * inv_n;
         if constexpr (STATS) {
             for (int k = 0; k < nrep; ++k) {
-                const float d = m - src(k)[i];
+                const float d = m - rep1(k, i);
                 gsum += (double)d * (double)d;
             }
             msum += (double)m * (double)m;
@@ -643,14 +697,21 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
             if constexpr (ADAM) st<NT>(b4 + v, f32x4{B4[0], B4[1], B4[2], B4[3]});
             if constexpr (MODEL) st<NT>(m4 + v, bf16_rne4(pn));
         };
+        const int64_t vfo = (fo + h) >> 2;  // peers' index of the body's first group of four
+        auto rep4 = [&](int k, int v) -> f32x4 {
+            if constexpr (W16) {
+                if (k == lr) return bf16_widen4(bf16_rne4(ld<NT>(p4 + v)));
+                return wire4<true, NT>(a.x[k], vfo + v);
+            } else {  // same element type on both sides: select the base pointer, one load either way
+                const f32x4 *b = k == lr ? p4 : reinterpret_cast<const f32x4 *>(a.x[k]) + vfo;
+                return ld<NT>(b + v);
+            }
+        };
         if constexpr (NREP > 0) {
-            const f32x4 *x4[NREP];
-#pragma unroll
-            for (int k = 0; k < NREP; ++k) x4[k] = reinterpret_cast<const f32x4 *>(src(k) + h);
             for (int v = tid; v < nv; v += kThreads) {
                 f32x4 x[NREP];
 #pragma unroll
-                for (int k = 0; k < NREP; ++k) x[k] = ld<NT>(x4[k] + v);
+                for (int k = 0; k < NREP; ++k) x[k] = rep4(k, v);
                 const gvec gv = ld<NT>(g4 + v);
                 const f32x4 av = ld<NT>(a4 + v);
                 f32x4 bv{};
@@ -667,11 +728,11 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
             }
         } else {
             for (int v = tid; v < nv; v += kThreads) {
-                f32x4 acc = ld<NT>(reinterpret_cast<const f32x4 *>(src(0) + h) + v);
-                for (int k = 1; k < nrep; ++k) acc = acc + ld<NT>(reinterpret_cast<const f32x4 *>(src(k) + h) + v);
+                f32x4 acc = rep4(0, v);
+                for (int k = 1; k < nrep; ++k) acc = acc + rep4(k, v);
                 const f32x4 m = acc * inv_n;
                 if constexpr (STATS) {
-                    for (int k = 0; k < nrep; ++k) stats4(m, reinterpret_cast<const f32x4 *>(src(k) + h)[v]);
+                    for (int k = 0; k < nrep; ++k) stats4(m, rep4(k, v));
                 }
                 const gvec gv = ld<NT>(g4 + v);
                 const f32x4 av = ld<NT>(a4 + v);
@@ -715,6 +776,12 @@ int launch_stats(const double *partials, double *slice_sums, const int32_t *rang
 }
 
 template <int NREP>
+int launch_mean16_n(const MeanArgs &ma, const MeanLaunch &a, void *stream) {
+    if (a.partials) return launch(mean_kernel<NREP, true, true, true>, a.n_chunks, stream, a.lds_pad, ma);
+    return launch(mean_kernel<NREP, false, true, true>, a.n_chunks, stream, a.lds_pad, ma);
+}
+
+template <int NREP>
 int launch_mean_n(const MeanArgs &ma, const MeanLaunch &a, void *stream) {
     if (a.partials) return a.nontemporal ? launch(mean_kernel<NREP, true, true>, a.n_chunks, stream, a.lds_pad, ma) : launch(mean_kernel<NREP, true, false>, a.n_chunks, stream, a.lds_pad, ma);
     return a.nontemporal ? launch(mean_kernel<NREP, false, true>, a.n_chunks, stream, a.lds_pad, ma) : launch(mean_kernel<NREP, false, false>, a.n_chunks, stream, a.lds_pad, ma);
@@ -732,6 +799,12 @@ int launch_copy(bool unpack, const TensorDesc *tensors, const CopyChunk *chunks,
                        : launch(copy_kernel<true, false, false>, n_chunks, stream, lds_pad, tensors, chunks, flat);
 }
 
+int launch_pack16(const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, uint16_t *flat16, bool nontemporal, int lds_pad,
+                  void *stream) {
+    return nontemporal ? launch(pack16_kernel<true>, n_chunks, stream, lds_pad, tensors, chunks, flat16)
+                       : launch(pack16_kernel<false>, n_chunks, stream, lds_pad, tensors, chunks, flat16);
+}
+
 int launch_mean(const MeanLaunch &a, void *stream) {
     MeanArgs ma{};
     for (int k = 0; k < a.n_replicas; ++k) ma.x[k] = a.x[k];
@@ -741,17 +814,26 @@ int launch_mean(const MeanLaunch &a, void *stream) {
     ma.inv_n = a.inv_n;
     ma.n = a.n_replicas;
     int rc;
-    switch (a.n_replicas) {
-        case 1: rc = launch_mean_n<1>(ma, a, stream); break;
-        case 2: rc = launch_mean_n<2>(ma, a, stream); break;
-        case 3: rc = launch_mean_n<3>(ma, a, stream); break;
-        case 4: rc = launch_mean_n<4>(ma, a, stream); break;
-        case 5: rc = launch_mean_n<5>(ma, a, stream); break;
-        case 6: rc = launch_mean_n<6>(ma, a, stream); break;
-        case 7: rc = launch_mean_n<7>(ma, a, stream); break;
-        case 8: rc = launch_mean_n<8>(ma, a, stream); break;
-        case 16: rc = launch_mean_n<16>(ma, a, stream); break;
-        default: rc = launch_mean_n<0>(ma, a, stream); break;
+    if (a.wire16) {
+        switch (a.n_replicas) {
+            case 4: rc = launch_mean16_n<4>(ma, a, stream); break;
+            case 8: rc = launch_mean16_n<8>(ma, a, stream); break;
+            case 16: rc = launch_mean16_n<16>(ma, a, stream); break;
+            default: rc = launch_mean16_n<0>(ma, a, stream); break;
+        }
+    } else {
+        switch (a.n_replicas) {
+            case 1: rc = launch_mean_n<1>(ma, a, stream); break;
+            case 2: rc = launch_mean_n<2>(ma, a, stream); break;
+            case 3: rc = launch_mean_n<3>(ma, a, stream); break;
+            case 4: rc = launch_mean_n<4>(ma, a, stream); break;
+            case 5: rc = launch_mean_n<5>(ma, a, stream); break;
+            case 6: rc = launch_mean_n<6>(ma, a, stream); break;
+            case 7: rc = launch_mean_n<7>(ma, a, stream); break;
+            case 8: rc = launch_mean_n<8>(ma, a, stream); break;
+            case 16: rc = launch_mean_n<16>(ma, a, stream); break;
+            default: rc = launch_mean_n<0>(ma, a, stream); break;
+        }
     }
     if (rc != 0 || !a.partials) return rc;
     return launch_stats(a.partials, a.slice_sums, a.layer_ranges, a.n_layers, a.n_replicas, a.stats, stream);
@@ -779,9 +861,12 @@ int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *t
 template <bool A, bool G, bool M>
 static int launch_fused_t(const FusedLaunch &f, const FusedArgs &fa, void *stream) {
     const bool st = f.partials != nullptr;
-#define DDP_FUSED(NR)                                                                                        \
-    return st ? launch(fused_kernel<A, G, M, NR, true>, f.n_chunks, stream, f.lds_pad, fa)                   \
-              : launch(fused_kernel<A, G, M, NR, false>, f.n_chunks, stream, f.lds_pad, fa);
+#define DDP_FUSED(NR)                                                                                                       \
+    if (f.wire16)                                                                                                           \
+        return st ? launch(fused_kernel<A, G, M, NR, true, true>, f.n_chunks, stream, f.lds_pad, fa)                        \
+                  : launch(fused_kernel<A, G, M, NR, false, true>, f.n_chunks, stream, f.lds_pad, fa);                      \
+    return st ? launch(fused_kernel<A, G, M, NR, true, false>, f.n_chunks, stream, f.lds_pad, fa)                           \
+              : launch(fused_kernel<A, G, M, NR, false, false>, f.n_chunks, stream, f.lds_pad, fa);
     switch (f.n_replicas) {
         case 4: DDP_FUSED(4)
         case 8: DDP_FUSED(8)

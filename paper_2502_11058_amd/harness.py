@@ -21,12 +21,15 @@ from . import workloads as W
 class DeviceReplica:
     def __init__(self, w: W.Workload, device: int = 0, options: Optional[Dict[str, int]] = None, arena_offset: int = 0,
                  grad_dtype: Optional[str] = None, policy: Optional[str] = None, n_peers: Optional[int] = None,
-                 region_skew: int = 0, placement_probe: Optional[bool] = None):
+                 region_skew: int = 0, placement_probe: Optional[bool] = None, wire16: bool = False):
         """Schedules, allocates, registers.  arena_offset: elements skipped at the start of every arena (tests use
         it to break 16-byte alignment).  policy: schedule policy (default: the workload's).  region_skew: extra bytes
         (multiple of 256) by which each successive region of the slab is shifted off its 2 MiB boundary.
         placement_probe: time the update kernel on the freshly zeroed slab and, if a re-allocation lands on
-        physical memory that streams faster, keep that one (default: on for models of a billion parameters or more)."""
+        physical memory that streams faster, keep that one (default: on for models of a billion parameters or more).
+        wire16: also allocate bf16 flat and peer buffers for the bf16-on-the-wire entry points (step/fused_step then
+        take wire16=True)."""
+        self.wire16 = wire16
         self.w = w
         self.dev = torch.device("cuda", device)
         torch.cuda.set_device(self.dev)
@@ -76,7 +79,7 @@ class DeviceReplica:
         import gc
         self.ctx.close()
         self.ctx._keep = []
-        for name in ("slab", "a_sync", "a_s0", "a_s1", "a_grad", "a_model", "flat", "stats", "peers", "sync", "model", "grad", "s0", "s1"):
+        for name in ("slab", "a_sync", "a_s0", "a_s1", "a_grad", "a_model", "flat", "stats", "peers", "flat16", "peers16", "sync", "model", "grad", "s0", "s1"):
             setattr(self, name, None)
         gc.collect()
         torch.cuda.empty_cache()
@@ -113,6 +116,9 @@ class DeviceReplica:
             regions.append(("model", torch.bfloat16, P + o))
         regions.append(("flat", torch.float32, smax))
         regions += [(f"peer{k}", torch.float32, smax) for k in range(n_peers)]
+        if self.wire16:
+            regions.append(("flat16", torch.bfloat16, smax))
+            regions += [(f"peer16_{k}", torch.bfloat16, smax) for k in range(n_peers)]
         regions.append(("stats", torch.float64, 2 * max_layers + 2))
         ALIGN = 2 << 20
         pos, place = 0, {}
@@ -133,6 +139,8 @@ class DeviceReplica:
         self.a_grad, self.a_model = region("grad"), region("model")
         self.flat, self.stats = region("flat"), region("stats")
         self.peers = [region(f"peer{k}") for k in range(n_peers)]
+        self.flat16 = region("flat16")
+        self.peers16 = [region(f"peer16_{k}") for k in range(n_peers)] if self.wire16 else []
         self.offsets = np.concatenate([[0], np.cumsum(self.numel)]).astype(np.int64) + o
 
         def views(a):
@@ -169,25 +177,43 @@ class DeviceReplica:
             W.normal_(p[:n], w.sigma_drift, W.seed_for(w.base_seed, w.name, "peer", iteration, k, 0))
             p[:n].add_(base_flat[:n])
 
+    def fill_peers16_from(self, base_flat: torch.Tensor, iteration: int, n: int) -> None:
+        """bf16 peer k = bf16_rne(base_flat[:n] + N(0, sigma_drift)): the fp32 peers of fill_peers_from, rounded
+        (torch's cast is round-to-nearest-even).  Leaves the fp32 peer buffers holding the unrounded values."""
+        self.fill_peers_from(base_flat, iteration, n)
+        for p, q in zip(self.peers, self.peers16):
+            q[:n].copy_(p[:n])
+
     # -- the iteration ----------------------------------------------------------------------------------------
     def opt_struct(self, step: int) -> B.ddp_opt:
         w = self.w
         return B.make_opt(w.optimizer, w.lr, step, momentum=w.momentum, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
                           weight_decay=w.weight_decay)
 
-    def step(self, r: int, local_rank: int = 0, with_stats: bool = True, stream=None) -> None:
+    def step(self, r: int, local_rank: int = 0, with_stats: bool = True, stream=None, wire16: bool = False) -> None:
         """Iteration r (0-based): pack -> partial average -> unpack -> local update, all enqueued on one stream."""
         slot = r % len(self.sets)
         c = self.ctx
+        if wire16:
+            c.ddp_pack_wire16(slot, self.flat16, stream)
+            c.ddp_partial_average_wire16(slot, self.flat16, self.peers16, len(self.peers16) + 1, local_rank, self.flat,
+                                         self.stats if with_stats else None, stream)
+            c.ddp_unpack(slot, self.flat, stream)
+            c.ddp_local_update(self.opt_struct(r + 1), stream)
+            return
         c.ddp_pack(slot, self.flat, stream)
         c.ddp_partial_average(slot, self.flat, self.peers, len(self.peers) + 1, local_rank, self.flat,
                               self.stats if with_stats else None, stream)
         c.ddp_unpack(slot, self.flat, stream)
         c.ddp_local_update(self.opt_struct(r + 1), stream)
 
-    def fused_step(self, r: int, local_rank: int = 0, with_stats: bool = True, stream=None) -> None:
+    def fused_step(self, r: int, local_rank: int = 0, with_stats: bool = True, stream=None, wire16: bool = False) -> None:
         """Iteration r through the fused entry point: same result, no flat round trip for the local replica."""
         slot = r % len(self.sets)
+        if wire16:
+            self.ctx.ddp_fused_sync_update_wire16(slot, self.peers16, len(self.peers16) + 1, local_rank,
+                                                  self.stats if with_stats else None, self.opt_struct(r + 1), stream)
+            return
         self.ctx.ddp_fused_sync_update(slot, self.peers, len(self.peers) + 1, local_rank, self.stats if with_stats else None,
                                        self.opt_struct(r + 1), stream)
 

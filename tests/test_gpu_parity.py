@@ -80,12 +80,12 @@ class Tally:
 
 
 def run_trajectory(oracle, w, policy=None, iters=None, arena_offset=0, options=None, order=0, grad_dtype=None,
-                   check_every=1, threads=16, fused=False):
+                   check_every=1, threads=16, fused=False, wire16=False):
     from paper_2502_11058_amd.harness import DeviceReplica
     _need_gpu()
     oracle.set_threads(threads)
     iters = iters or w.iterations
-    rep = DeviceReplica(w, 0, options=options, arena_offset=arena_offset, grad_dtype=grad_dtype, policy=policy)
+    rep = DeviceReplica(w, 0, options=options, arena_offset=arena_offset, grad_dtype=grad_dtype, policy=policy, wire16=wire16)
     rep.init_params()
     N, H = w.n_replicas, w.period
     fp, bp, comm = W.synthetic_times(w)
@@ -129,21 +129,56 @@ def run_trajectory(oracle, w, policy=None, iters=None, arena_offset=0, options=N
             # one call does average + update; peers from an independent gather, statistics and state against the oracle
             dev_flat = torch.cat([rep.sync[t] for t in order_t]) if total else rep.flat[:0]
             local_host = _np(dev_flat)
-            rep.fill_peers_from(dev_flat, r, total)
-            peers_host = [_np(p[:total]) for p in rep.peers]
+            if wire16:
+                local_host = oracle.bf16_rne(local_host)          # what the local replica contributes
+                rep.fill_peers16_from(dev_flat, r, total)
+                peers_host = [_np(p[:total]) for p in rep.peers16]
+            else:
+                rep.fill_peers_from(dev_flat, r, total)
+                peers_host = [_np(p[:total]) for p in rep.peers]
             rep.fill_grads(r)
             grads = [_np(g) for g in rep.grad]
             rep.stats.fill_(-1.0)
-            rep.ctx.ddp_fused_sync_update(slot, rep.peers, N, rank, rep.stats, rep.opt_struct(r + 1))
+            if wire16:
+                rep.ctx.ddp_fused_sync_update_wire16(slot, rep.peers16, N, rank, rep.stats, rep.opt_struct(r + 1))
+            else:
+                rep.ctx.ddp_fused_sync_update(slot, rep.peers, N, rank, rep.stats, rep.opt_struct(r + 1))
             reps = peers_host[:rank] + [local_host] + peers_host[rank:]
-            mean_ref = oracle.mean(reps) if total else local_host
+            o_mean, o_stats = (oracle.mean_wire16, oracle.layer_stats_wire16) if wire16 else (oracle.mean, oracle.layer_stats)
+            mean_ref = o_mean(reps) if total else np.zeros(0, np.float32)
             st = _np(rep.stats)
             for i, (b, e) in enumerate(ranges):
-                g, m = oracle.layer_stats(reps, mean_ref, b, e)
+                g, m = o_stats(reps, mean_ref, b, e)
                 assert st[2 * i] == pytest.approx(g, rel=1e-10, abs=1e-300), f"fused gamma r={r} layer {S[i]}"
                 assert st[2 * i + 1] == pytest.approx(m, rel=1e-10), f"fused msq r={r} layer {S[i]}"
-            wk.sync(S, peers_host, rank)
+            wk.sync(S, peers_host, rank, wire16=wire16)
             wk.local_update(grads, r + 1)
+        elif wire16:
+            # bf16 on the wire: pack rounds, the average widens; every stage against the oracle on the same bytes
+            dev_flat = torch.cat([rep.sync[t] for t in order_t]) if total else rep.flat[:0]
+            local16 = oracle.bf16_rne(_np(dev_flat))
+            rep.flat16.view(torch.int16).fill_(-1)
+            rep.ctx.ddp_pack_wire16(slot, rep.flat16)
+            assert np.array_equal(_np(rep.flat16[:total]), local16), f"pack16 r={r}"
+            assert np.array_equal(oracle.pack_wire16([_np(rep.sync[t]) for t in order_t], [off[t] for t in order_t], total), local16)
+            assert int(rep.flat16.view(torch.int16)[total:].ne(-1).sum()) == 0, "pack16 wrote past the slot"
+            rep.fill_peers16_from(dev_flat, r, total)
+            peers_host = [_np(p[:total]) for p in rep.peers16]
+            out.fill_(float("nan"))
+            rep.stats.fill_(-1.0)
+            rep.ctx.ddp_partial_average_wire16(slot, rep.flat16, rep.peers16, N, rank, out, rep.stats)
+            reps = peers_host[:rank] + [local16] + peers_host[rank:]
+            mean_ref = oracle.mean_wire16(reps) if total else np.zeros(0, np.float32)
+            assert np.array_equal(_bits(_np(out[:total])), _bits(mean_ref)), f"mean16 r={r}"
+            st = _np(rep.stats)
+            for i, (b, e) in enumerate(ranges):
+                g, m = oracle.layer_stats_wire16(reps, mean_ref, b, e)
+                assert st[2 * i] == pytest.approx(g, rel=1e-10, abs=1e-300), f"gamma16 r={r} layer {S[i]}"
+                assert st[2 * i + 1] == pytest.approx(m, rel=1e-10), f"msq16 r={r} layer {S[i]}"
+            rep.ctx.ddp_unpack(slot, out)
+            wk.sync(S, peers_host, rank, wire16=True)
+            if order == 0:
+                update_both(r)
         else:
             # pack: against an independent gather of the same device tensors (torch.cat in the oracle's order)
             dev_flat = torch.cat([rep.sync[t] for t in order_t]) if total else rep.flat[:0]
@@ -273,6 +308,25 @@ def test_fused_odd_shapes(oracle, arena_offset):
     assert t.frac() == 1.0
     w = W.odd(optimizer="sgdm", param_dtype="f32", n_replicas=3, period=3)
     run_trajectory(oracle, w, fused=True, arena_offset=arena_offset, policy="full")
+
+
+@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("name,kw", [("tiny", {}), ("small_llama", {}), ("small_llama", {"n_replicas": 5, "period": 3}),
+                                     ("small_llama", {"n_replicas": 16}), ("small_llama", {"n_replicas": 4, "period": 2})])
+def test_bf16_wire_matches_the_oracle(oracle, name, kw, fused):
+    w = W.WORKLOADS[name](**kw)
+    t = run_trajectory(oracle, w, fused=fused, wire16=True, iters=8)
+    assert t.frac() == 1.0
+
+
+@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("arena_offset", [0, 1, 2, 3])
+def test_bf16_wire_odd_shapes(oracle, arena_offset, fused):
+    w = W.odd(optimizer="adamw", param_dtype="bf16", n_replicas=4, period=2)
+    t = run_trajectory(oracle, w, fused=fused, wire16=True, arena_offset=arena_offset, options={"update_chunk": 1024, "mean_chunk": 2048})
+    assert t.frac() == 1.0
+    w = W.odd(optimizer="sgdm", param_dtype="f32", n_replicas=3, period=3)
+    run_trajectory(oracle, w, fused=fused, wire16=True, arena_offset=arena_offset, policy="full")
 
 
 @pytest.mark.parametrize("options", [
