@@ -97,6 +97,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stats", action="store_true", help="skip the per-layer statistics in the average")
     ap.add_argument("--option", action="append", default=[], help="library option name=value (repeatable)")
+    ap.add_argument("--wire16", action="store_true",
+                    help="also time the bf16-on-the-wire entry points (four calls and fused); reported in an extra "
+                         "\"wire16\" object, never in value")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 4 plain elementwise copies of 1 GiB (torch.add(src, 0, out=dst)) before the timed region, "
                          "as the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
@@ -132,13 +135,16 @@ def main() -> int:
             torch.cuda.empty_cache()
         print(json.dumps({"placement_study_update_GBps": res, "workload": w.name}))
         return 0
-    rep = DeviceReplica(w, 0, options=options, policy=args.policy)
+    rep = DeviceReplica(w, 0, options=options, policy=args.policy, wire16=args.wire16)
     rep.init_params()
     rep.fill_grads(0)
     # peers: slot 0's packed local values + seeded drift; later slots reuse the staged bytes (same distribution)
     rep.ctx.ddp_pack(0, rep.flat)
     torch.cuda.synchronize()
-    rep.fill_peers_from(rep.flat, 0, rep.flat.numel())
+    if args.wire16:
+        rep.fill_peers16_from(rep.flat, 0, rep.flat.numel())
+    else:
+        rep.fill_peers_from(rep.flat, 0, rep.flat.numel())
     torch.cuda.synchronize()
 
     if args.calibrate_copy:
@@ -222,6 +228,28 @@ def main() -> int:
              "value_vs_4call_bytes": total_bytes / wall_f / 1e9, "own_alg_bytes_per_step_avg": fused_bytes / args.steps,
              "GB/s_on_own_bytes": fused_bytes / wall_f / 1e9, "params_per_s": w.n_params * args.steps / wall_f}
 
+    # ---- optional pass 4: bf16 on the wire (2 bytes per peer element instead of 4) ---------------------------------
+    wire16 = None
+    if args.wire16:
+        wire16 = {}
+        r3 = r2 + H + args.steps
+        for name, fn in (("four_calls", rep.step), ("fused", rep.fused_step)):
+            for r in range(r3, r3 + H):
+                fn(r, with_stats=with_stats, wire16=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for r in range(r3 + H, r3 + H + args.steps):
+                fn(r, with_stats=with_stats, wire16=True)
+            torch.cuda.synchronize()
+            wl = time.perf_counter() - t0
+            S_sum = float(sum(rep.slot_numel[r % H] for r in range(r3 + H, r3 + H + args.steps)))
+            upd = upd_per_param * w.n_params * args.steps
+            # four calls: pack 4S+2S, average 2NS+4S, unpack 4S + (4+2)S; fused: 2(N-1)S on top of the update
+            own = (6 + 2 * w.n_replicas + 4 + 4 + 4 + (2 if rep.bf16 else 0)) * S_sum + upd if name == "four_calls" \
+                else 2 * (w.n_replicas - 1) * S_sum + upd
+            wire16[name] = {"ms_per_step": 1e3 * wl / args.steps, "own_alg_bytes_per_step_avg": own / args.steps,
+                            "GB/s_on_own_bytes": own / wl / 1e9, "params_per_s": w.n_params * args.steps / wl}
+
     out = {
         "metric": "partial-sync+update step: achieved HBM GB/s & % of peak; params/s",
         "value": gbs, "unit": "GB/s", "pct_of_peak": 100.0 * gbs / HBM_PEAK_GBS,
@@ -234,6 +262,8 @@ def main() -> int:
                    "placement_probe_GBps": [round(x, 1) for x in rep.placement["probe_GBps"]]},
         "kernels": kernels, "roofline": roofline, "fused": fused,
     }
+    if wire16 is not None:
+        out["wire16"] = wire16
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(rep, w)
     print(json.dumps(out))

@@ -710,8 +710,23 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
         if constexpr (NREP > 0) {
             for (int v = tid; v < nv; v += kThreads) {
                 f32x4 x[NREP];
+                if constexpr (W16 && NREP > 1) {
+                    // The local replica has another element type than the peers, so a pointer select cannot cover
+                    // it, and a branch per replica would serialise the loads.  Load the N-1 peers unconditionally,
+                    // then put the local value at position lr with register selects (lr is wave-uniform).
+                    f32x4 pv[NREP - 1];
 #pragma unroll
-                for (int k = 0; k < NREP; ++k) x[k] = rep4(k, v);
+                    for (int j = 0; j < NREP - 1; ++j) pv[j] = wire4<true, NT>(a.x[j + (j >= lr ? 1 : 0)], vfo + v);
+                    const f32x4 loc = bf16_widen4(bf16_rne4(ld<NT>(p4 + v)));
+#pragma unroll
+                    for (int k = 0; k < NREP; ++k) {
+                        const f32x4 before = pv[k < NREP - 1 ? k : NREP - 2], after = pv[k > 0 ? k - 1 : 0];
+                        x[k] = k == lr ? loc : (k < lr ? before : after);
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < NREP; ++k) x[k] = rep4(k, v);
+                }
                 const gvec gv = ld<NT>(g4 + v);
                 const f32x4 av = ld<NT>(a4 + v);
                 f32x4 bv{};

@@ -21,7 +21,7 @@ def test_bad_arguments_are_reported_not_launched(oracle):
     from paper_2502_11058_amd.harness import DeviceReplica
     assert torch.cuda.is_available(), "no GPU visible"
     w = W.tiny()
-    rep = DeviceReplica(w, 0)
+    rep = DeviceReplica(w, 0, wire16=True)
     rep.init_params()
     c, N = rep.ctx, w.n_replicas
     before = rep.a_sync.clone()
@@ -37,6 +37,17 @@ def test_bad_arguments_are_reported_not_launched(oracle):
     _expect(1, c.ddp_partial_average, 0, flat, rep.peers, N, 0, rep.peers[0])          # output overlaps a peer
     _expect(1, c.ddp_partial_average, 0, flat, rep.peers, N, 0, flat[4:])              # partial overlap with the input
     _expect(3, c.ddp_unpack, 0, flat[2:])
+    f16, p16 = rep.flat16, rep.peers16                                     # bf16-on-the-wire entry points
+    _expect(1, c.ddp_pack_wire16, 9, f16)
+    _expect(3, c.ddp_pack_wire16, 0, f16[1:])
+    _expect(1, c.ddp_partial_average_wire16, 0, f16, p16, 0, 0, flat)
+    _expect(1, c.ddp_partial_average_wire16, 0, f16, p16, N, N, flat)
+    _expect(1, c.ddp_partial_average_wire16, 0, f16, None, N, 0, flat)
+    _expect(3, c.ddp_partial_average_wire16, 0, f16, [p[1:] for p in p16], N, 0, flat)
+    _expect(1, c.ddp_partial_average_wire16, 0, f16, p16, N, 0, f16.view(torch.float32))      # no in-place form
+    _expect(1, c.ddp_partial_average_wire16, 0, f16, p16, N, 0, p16[0].view(torch.float32))
+    _expect(1, c.ddp_fused_sync_update_wire16, 0, p16, N, N, None, B.make_opt("sgdm", 0.01, 1))
+    _expect(3, c.ddp_fused_sync_update_wire16, 0, [p[1:] for p in p16], N, 0, None, B.make_opt("sgdm", 0.01, 1))
     _expect(7, c.ddp_local_update, B.make_opt("adamw", 1e-3, 0))           # no second moment registered (checked first)
     opt = B.make_opt("sgdm", 0.01, 1)
     opt.kind = 7

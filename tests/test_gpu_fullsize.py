@@ -40,7 +40,7 @@ def _sample_positions(rep, n_random, seed):
     return np.unique(np.concatenate(pos)) + int(rep.offsets[0])
 
 
-def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000, fused=False):
+def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000, fused=False, wire16=False):
     from paper_2502_11058_amd.harness import DeviceReplica
     _need_gpu()
     oracle.set_threads(16)
@@ -48,10 +48,11 @@ def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000,
     torch.cuda.empty_cache()
     free, total_mem = torch.cuda.mem_get_info()
     progress(f"[{w.name}] HBM free {free / 1e9:.1f} GB of {total_mem / 1e9:.1f} GB")
-    rep = DeviceReplica(w, 0)
+    rep = DeviceReplica(w, 0, wire16=wire16)
     rep.init_params()
     N, H = w.n_replicas, w.period
     dev = rep.dev
+    o_mean, o_stats = (oracle.mean_wire16, oracle.layer_stats_wire16) if wire16 else (oracle.mean, oracle.layer_stats)
     gi_host = _sample_positions(rep, n_random, 7)
     gi = torch.from_numpy(gi_host).to(dev)
     tensor_of = np.searchsorted(rep.offsets, gi_host, side="right") - 1
@@ -75,25 +76,56 @@ def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000,
         rep.fill_grads(r)
         g_s = _np(rep.a_grad[gi])
         base = torch.cat([rep.sync[t] for t in order_t])       # independent gather (harness), the peers' base
-        rep.fill_peers_from(base, r, total)
-        if fused:
-            # one launch: only the end state and the statistics are observable
-            x_s = [_np(p[fi]) for p in rep.peers]
-            reps_s = x_s[:rank] + [_np(base[fi])] + x_s[rank:]
-            mean_s = oracle.mean(reps_s)
+        if wire16:
+            rep.fill_peers16_from(base, r, total)
+        else:
+            rep.fill_peers_from(base, r, total)
+        wire = rep.peers16 if wire16 else rep.peers                      # what the peers put on the wire ...
+        local = (lambda x: oracle.bf16_rne(_np(x))) if wire16 else _np   # ... and what the local replica contributes
+        if fused or wire16:
+            # the end state and the statistics; with the four bf16 calls also every element of pack and average
+            x_s = [_np(p[fi]) for p in wire]
+            reps_s = x_s[:rank] + [local(base[fi])] + x_s[rank:]
+            mean_s = o_mean(reps_s)
             unsched_before = None
             i = int(np.argmin([int(lbeg[j + 1] - lbeg[j]) for j in range(len(S))]))
             b, e = int(lbeg[i]), int(lbeg[i + 1])
             layer_reps = None
             if e - b <= stats_layer_cap:
-                xs = [_np(p[b:e]) for p in rep.peers]
-                layer_reps = xs[:rank] + [_np(base[b:e])] + xs[rank:]
-            del base
+                xs = [_np(p[b:e]) for p in wire]
+                layer_reps = xs[:rank] + [local(base[b:e])] + xs[rank:]
             rep.stats.fill_(-1.0)
-            rep.ctx.ddp_fused_sync_update(slot, rep.peers, N, rank, rep.stats, rep.opt_struct(r + 1))
+            if fused:
+                del base
+                if wire16:
+                    rep.ctx.ddp_fused_sync_update_wire16(slot, rep.peers16, N, rank, rep.stats, rep.opt_struct(r + 1))
+                else:
+                    rep.ctx.ddp_fused_sync_update(slot, rep.peers, N, rank, rep.stats, rep.opt_struct(r + 1))
+            else:
+                rep.flat16.view(torch.int16).fill_(-1)
+                rep.ctx.ddp_pack_wire16(slot, rep.flat16)
+                step_n = 1 << 28
+                for b0 in range(0, total, step_n):      # torch's fp32 -> bf16 cast is round-to-nearest-even as well
+                    e0 = min(total, b0 + step_n)
+                    assert torch.equal(rep.flat16[b0:e0].view(torch.int16), base[b0:e0].to(torch.bfloat16).view(torch.int16)), f"pack16 r={r} at {b0}"
+                assert np.array_equal(_np(rep.flat16[fi]), local(base[fi])), f"pack16 (oracle samples) r={r}"
+                del base
+                rep.ctx.ddp_partial_average_wire16(slot, rep.flat16, rep.peers16, N, rank, rep.flat, rep.stats)
+                seq = rep.peers16[:rank] + [rep.flat16] + rep.peers16[rank:]
+                for b0 in range(0, total, step_n):      # widening is exact: an independent fp32 sum of every element
+                    e0 = min(total, b0 + step_n)
+                    acc = seq[0][b0:e0].float()
+                    for k in range(1, N):
+                        acc.add_(seq[k][b0:e0].float())
+                    acc.mul_(inv_n)
+                    assert torch.equal(rep.flat[b0:e0].view(torch.int32), acc.view(torch.int32)), f"mean16 (all elements) r={r} at {b0}"
+                del acc, seq
+                assert np.array_equal(_bits(_np(rep.flat[fi])), _bits(mean_s)), f"mean16 (oracle samples) r={r}"
+                rep.ctx.ddp_unpack(slot, rep.flat)
+                rep.ctx.ddp_local_update(rep.opt_struct(r + 1))
             if layer_reps is not None:
                 st = _np(rep.stats)
-                g, m = oracle.layer_stats(layer_reps, oracle.mean(layer_reps), 0, e - b)
+                g, m = o_stats(layer_reps, o_mean(layer_reps), 0, e - b)
                 assert st[2 * i] == pytest.approx(g, rel=1e-10), f"fused gamma r={r} layer {S[i]}"
                 assert st[2 * i + 1] == pytest.approx(m, rel=1e-10), f"fused msq r={r} layer {S[i]}"
                 del layer_reps, xs
@@ -192,6 +224,12 @@ def test_llama2_7b_sampled_trajectory(oracle):
 @pytest.mark.timeout(1500)
 def test_llama2_7b_fused_sampled_trajectory(oracle):
     assert run_sampled(oracle, W.llama2_7b(), iters=8, fused=True) == 1.0
+
+
+@pytest.mark.timeout(1500)
+@pytest.mark.parametrize("fused", [False, True])
+def test_llama2_7b_bf16_wire_sampled_trajectory(oracle, fused):
+    assert run_sampled(oracle, W.llama2_7b(), iters=4, fused=fused, wire16=True) == 1.0
 
 
 @pytest.mark.timeout(1500)
