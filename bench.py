@@ -100,6 +100,11 @@ def main() -> int:
     ap.add_argument("--wire16", action="store_true",
                     help="also time the bf16-on-the-wire entry points (four calls and fused); reported in an extra "
                          "\"wire16\" object, never in value")
+    ap.add_argument("--overlap", action="store_true",
+                    help="also time the layer-wise launches of Sec. 3.2 on a side stream under a synthetic backward pass "
+                         "(bf16 matrix products standing in for each layer's BP); extra \"overlap\" object, never in value")
+    ap.add_argument("--overlap-mm", type=int, default=4096, metavar="D",
+                    help="edge of the square bf16 products of --overlap (4096: one product fills the 256 CUs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 4 plain elementwise copies of 1 GiB (torch.add(src, 0, out=dst)) before the timed region, "
                          "as the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
@@ -250,6 +255,43 @@ def main() -> int:
             wire16[name] = {"ms_per_step": 1e3 * wl / args.steps, "own_alg_bytes_per_step_avg": own / args.steps,
                             "GB/s_on_own_bytes": own / wl / 1e9, "params_per_s": w.n_params * args.steps / wl}
 
+    # ---- optional pass 5: layer-wise launches under a synthetic backward pass (Sec. 3.2) ----------------------------
+    overlap = None
+    if args.overlap:
+        side = torch.cuda.Stream()
+        D = args.overlap_mm
+        A = torch.randn(D, D, device=rep.dev, dtype=torch.bfloat16)
+        Bm = torch.randn(D, D, device=rep.dev, dtype=torch.bfloat16)
+        Cm = torch.empty(D, D, device=rep.dev, dtype=torch.bfloat16)
+        lay = w.layer_numel()
+        # stand-in for a layer's BP: 4 flop per parameter and token, 4096 tokens, as D^3 products
+        n_mm = [max(1, round(4 * n * 4096 / (2 * 4096 ** 3))) for n in lay]
+
+        def bp(l):
+            for _ in range(n_mm[l]):
+                torch.mm(A, Bm, out=Cm)
+
+        def timed(fn):
+            for r in range(H):
+                fn(r)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for r in range(args.steps):
+                fn(r)
+            torch.cuda.synchronize()
+            return 1e3 * (time.perf_counter() - t0) / args.steps
+
+        r4 = 10_000
+        bp_ms = timed(lambda r: [bp(l) for l in range(w.n_layers - 1, -1, -1)])
+        fused_ms = timed(lambda r: rep.fused_step(r4 + r, with_stats=with_stats))
+        serial_ms = timed(lambda r: rep.layerwise_step(r4 + r, torch.cuda.current_stream(), backward=lambda l: None,
+                                                       with_stats=with_stats))
+        both_ms = timed(lambda r: rep.layerwise_step(r4 + r, side, backward=bp, with_stats=with_stats))
+        overlap = {"synthetic_bp_ms": bp_ms, "fused_one_launch_ms": fused_ms, "fused_layerwise_same_stream_ms": serial_ms,
+                   "bp_with_layerwise_sync_on_side_stream_ms": both_ms,
+                   "hidden_fraction_of_sync_update": (bp_ms + serial_ms - both_ms) / serial_ms,
+                   "bp_flop_per_step": float(sum(n_mm)) * 2 * D ** 3, "product_edge": D}
+
     out = {
         "metric": "partial-sync+update step: achieved HBM GB/s & % of peak; params/s",
         "value": gbs, "unit": "GB/s", "pct_of_peak": 100.0 * gbs / HBM_PEAK_GBS,
@@ -264,6 +306,8 @@ def main() -> int:
     }
     if wire16 is not None:
         out["wire16"] = wire16
+    if overlap is not None:
+        out["overlap"] = overlap
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(rep, w)
     print(json.dumps(out))

@@ -225,6 +225,26 @@ int ddp_partial_average_wire16(ddp_ctx *ctx, int slot, const uint16_t *flat_loca
 int ddp_fused_sync_update_wire16(ddp_ctx *ctx, int slot, const uint16_t *const *peers16, int N, int local_rank,
                                  double *layer_stats, const ddp_opt *opt, void *stream);
 
+/* Layer-wise launches for overlap with back-propagation (Sec. 3.2: the synchronisation of a layer starts as soon as
+ * its backward pass has produced its gradient, while the layers below are still in BP; Algorithm 1 per layer).
+ * Both calls restrict their whole-model counterpart to the registered layers [layer_first, layer_first + layer_count):
+ *
+ * ddp_local_update_layers:      ddp_local_update on the tensors of those layers only.
+ * ddp_fused_sync_update_layers: ddp_fused_sync_update (wire_dtype DDP_F32: peers are fp32 buffers) or
+ *                               ddp_fused_sync_update_wire16 (DDP_BF16: bf16 buffers) on those layers only: the ones the
+ *                               slot schedules are averaged and updated, the others updated.  layer_stats has the layout of
+ *                               the whole-slot call (two doubles per layer of the slot, flat order); only the entries of
+ *                               scheduled layers inside the range are written.
+ *
+ * Calling either for a partition of [0, L) into ranges, once each, in any order, gives bit for bit the result of the
+ * whole-model call.  Calls for disjoint ranges may be in flight at the same time on different streams of the device
+ * (their reduction scratch is disjoint); calls whose ranges overlap must be ordered by the caller, as must the producer
+ * of the range's gradients and this call (stream order or an event).  Needs option dispatch_ways = 1 (the default),
+ * else DDP_ESTATE.  A range with layer_count == 0 is a no-op. */
+int ddp_local_update_layers(ddp_ctx *ctx, int layer_first, int layer_count, const ddp_opt *opt, void *stream);
+int ddp_fused_sync_update_layers(ddp_ctx *ctx, int slot, int layer_first, int layer_count, const void *const *peers,
+                                 int wire_dtype, int N, int local_rank, double *layer_stats, const ddp_opt *opt, void *stream);
+
 /* Message of the last failure on this context (ctx == NULL: last failure of ddp_create / ddp_schedule* in
  * this thread).  Never NULL; valid until the next call on the same context / thread. */
 const char *ddp_last_error(const ddp_ctx *ctx);

@@ -25,7 +25,8 @@ EXPORTS = [
     "ddp_schedule", "ddp_schedule_cost", "ddp_schedule_alg2_solutions", "ddp_schedule_fill_bubbles", "ddp_schedule_time_model", "ddp_create", "ddp_destroy", "ddp_set_option",
     "ddp_register_model", "ddp_set_schedule", "ddp_slot_numel", "ddp_slot_num_layers", "ddp_slot_num_tensors",
     "ddp_slot_layout", "ddp_pack", "ddp_partial_average", "ddp_unpack", "ddp_local_update", "ddp_fused_sync_update",
-    "ddp_pack_wire16", "ddp_partial_average_wire16", "ddp_fused_sync_update_wire16", "ddp_last_error",
+    "ddp_pack_wire16", "ddp_partial_average_wire16", "ddp_fused_sync_update_wire16",
+    "ddp_local_update_layers", "ddp_fused_sync_update_layers", "ddp_last_error",
 ]
 
 
@@ -73,6 +74,9 @@ def lib():
         l.ddp_pack_wire16.argtypes = l.ddp_pack.argtypes
         l.ddp_partial_average_wire16.argtypes = l.ddp_partial_average.argtypes
         l.ddp_fused_sync_update_wire16.argtypes = l.ddp_fused_sync_update.argtypes
+        l.ddp_local_update_layers.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(ddp_opt), C.c_void_p]
+        l.ddp_fused_sync_update_layers.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                                   C.c_void_p, C.POINTER(ddp_opt), C.c_void_p]
         l.ddp_schedule.argtypes = [C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7
         l.ddp_schedule_cost.argtypes = [C.c_int, C.c_int] + [C.c_void_p] * 5
         l.ddp_schedule_alg2_solutions.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -293,6 +297,17 @@ class Context:
     def ddp_fused_sync_update_wire16(self, slot: int, peers16, N: int, local_rank: int, layer_stats, opt: ddp_opt, stream=None) -> None:
         arr = _dev_ptrs(list(peers16)) if peers16 else None
         _check(lib().ddp_fused_sync_update_wire16(self._h, slot, None if arr is None else C.addressof(arr), N, local_rank,
+                                                  None if layer_stats is None else layer_stats.data_ptr(), C.byref(opt),
+                                                  _stream_handle(stream)), self._h)
+
+    def ddp_local_update_layers(self, layer_first: int, layer_count: int, opt: ddp_opt, stream=None) -> None:
+        _check(lib().ddp_local_update_layers(self._h, layer_first, layer_count, C.byref(opt), _stream_handle(stream)), self._h)
+
+    def ddp_fused_sync_update_layers(self, slot: int, layer_first: int, layer_count: int, peers, wire_dtype: int, N: int,
+                                     local_rank: int, layer_stats, opt: ddp_opt, stream=None) -> None:
+        arr = _dev_ptrs(list(peers)) if peers else None
+        _check(lib().ddp_fused_sync_update_layers(self._h, slot, layer_first, layer_count, None if arr is None else C.addressof(arr),
+                                                  wire_dtype, N, local_rank,
                                                   None if layer_stats is None else layer_stats.data_ptr(), C.byref(opt),
                                                   _stream_handle(stream)), self._h)
 

@@ -342,7 +342,7 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
         }
         max_mean_chunks = std::max(max_mean_chunks, ctx->n_update);  // the fused step keeps one partial per update chunk
         if (max_mean_chunks > 0) {
-            hipError_t e = hipMalloc((void **)&ctx->d_partials, ((size_t)max_mean_chunks + (size_t)ctx->L * 64) * 2 * sizeof(double));
+            hipError_t e = hipMalloc((void **)&ctx->d_partials, ((size_t)max_mean_chunks + (size_t)ctx->L * kStatSlices) * 2 * sizeof(double));
             if (e != hipSuccess) {
                 ctx->d_partials = nullptr;
                 for (auto &x : slots) free_slot(x);
@@ -538,20 +538,47 @@ static int make_scalars(ddp_ctx *ctx, const char *who, const ddp_opt *opt, Updat
     return DDP_OK;
 }
 
-extern "C" int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream) {
-    if (!ctx) return fail(nullptr, DDP_EINVAL, "ddp_local_update: ctx is NULL");
-    if (!ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_local_update: no model registered");
-    UpdateScalars s{};
-    int rc = make_scalars(ctx, "ddp_local_update", opt, s);
-    if (rc != DDP_OK) return rc;
-    if ((rc = check_device(ctx, "ddp_local_update")) != DDP_OK) return rc;
-    rc = launch_update(opt->kind, ctx->grad_dtype, ctx->param_dtype == DDP_BF16, ctx->d_tensors, ctx->d_update, ctx->n_update, s,
-                       ctx->nontemporal, ctx->update_lds, stream);
-    return after_launch(ctx, "ddp_local_update", rc);
+// Chunk range [c0, c1) of the update table that covers layers [first, first + count); needs the table in
+// registration order.
+static int layer_chunk_range(ddp_ctx *ctx, const char *who, int first, int count, int64_t *c0, int64_t *c1) {
+    const std::string w(who);
+    if (first < 0 || count < 0 || first > ctx->L || count > ctx->L - first)
+        return fail(ctx, DDP_EINVAL, w + ": layer range outside [0, " + std::to_string(ctx->L) + ")");
+    if (ctx->dispatch_ways != 1 && !(first == 0 && count == ctx->L))
+        return fail(ctx, DDP_ESTATE, w + ": a layer range needs the update table in registration order (option dispatch_ways = 1)");
+    *c0 = ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)first]];
+    *c1 = ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)(first + count)]];
+    return DDP_OK;
 }
 
-static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, const void *const *peers, int N, int local_rank,
-                      double *layer_stats, const ddp_opt *opt, void *stream) {
+static int local_update_impl(ddp_ctx *ctx, const char *who, bool whole, int first, int count, const ddp_opt *opt, void *stream) {
+    const std::string w(who);
+    if (!ctx) return fail(nullptr, DDP_EINVAL, w + ": ctx is NULL");
+    if (!ctx->registered) return fail(ctx, DDP_ESTATE, w + ": no model registered");
+    UpdateScalars s{};
+    int rc = make_scalars(ctx, who, opt, s);
+    if (rc != DDP_OK) return rc;
+    if ((rc = check_device(ctx, who)) != DDP_OK) return rc;
+    int64_t c0 = 0, c1 = ctx->n_update;
+    if (!whole && (rc = layer_chunk_range(ctx, who, first, count, &c0, &c1)) != DDP_OK) return rc;
+    if (c1 == c0) return DDP_OK;
+    rc = launch_update(opt->kind, ctx->grad_dtype, ctx->param_dtype == DDP_BF16, ctx->d_tensors, ctx->d_update + c0, c1 - c0, s,
+                       ctx->nontemporal, ctx->update_lds, stream);
+    return after_launch(ctx, who, rc);
+}
+
+extern "C" int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream) {
+    return local_update_impl(ctx, "ddp_local_update", true, 0, 0, opt, stream);
+}
+
+extern "C" int ddp_local_update_layers(ddp_ctx *ctx, int layer_first, int layer_count, const ddp_opt *opt, void *stream) {
+    return local_update_impl(ctx, "ddp_local_update_layers", false, layer_first, layer_count, opt, stream);
+}
+
+// whole: every layer (any dispatch order).  Otherwise layers [first, first + count) only: their chunks of the update
+// table, and the statistics of those of the slot's layers that fall in the range.
+static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, bool whole, int first, int count, const void *const *peers,
+                      int N, int local_rank, double *layer_stats, const ddp_opt *opt, void *stream) {
     int rc;
     const std::string w(who);
     const SlotTables *st = slot_of(ctx, slot, who, &rc);
@@ -563,6 +590,8 @@ static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, cons
     if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, w + ": local_rank out of range");
     if (N > 1 && !peers) return fail(ctx, DDP_EINVAL, w + ": peers is NULL");
     if (layer_stats && !aligned(layer_stats, 8)) return fail(ctx, DDP_EALIGN, w + ": layer_stats must be 8-byte aligned");
+    int64_t c0 = 0, c1 = ctx->n_update;
+    if (!whole && (rc = layer_chunk_range(ctx, who, first, count, &c0, &c1)) != DDP_OK) return rc;
     FusedLaunch f{};
     int p = 0;
     for (int k = 0; k < N; ++k) {
@@ -571,6 +600,7 @@ static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, cons
         if (st->numel > 0 && (rc = check_flat(ctx, q, who, "a peer buffer")) != DDP_OK) return rc;
         f.x[k] = q;
     }
+    if (c1 == c0) return DDP_OK;
     f.wire16 = wire16;
     f.n_replicas = N;
     f.local_rank = local_rank;
@@ -579,29 +609,69 @@ static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, cons
     f.grad_dtype = ctx->grad_dtype;
     f.with_model = ctx->param_dtype == DDP_BF16;
     f.tensors = ctx->d_tensors;
-    f.chunks = ctx->d_update;
-    f.n_chunks = ctx->n_update;
+    f.chunks = ctx->d_update + c0;
+    f.n_chunks = c1 - c0;
     f.tensor_flat_off = st->d_tensor_flat_off;
     f.tensor_chunk_base = ctx->d_tensor_chunk_base;
     f.chunk_elems = (int)ctx->update_chunk;
     f.s = s;
-    f.partials = (layer_stats && !st->layers.empty()) ? ctx->d_partials : nullptr;
-    f.slice_sums = ctx->d_slice_sums;
-    f.layer_ranges = st->d_fused_ranges;
-    f.n_layers = (int)st->layers.size();
-    f.stats = layer_stats;
     f.lds_pad = ctx->update_lds;
-    return after_launch(ctx, who, launch_fused(f, stream));
+    const int nl = (int)st->layers.size();
+    if (!layer_stats || nl == 0) return after_launch(ctx, who, launch_fused(f, stream));
+    f.partials = ctx->d_partials;
+    if (whole) {
+        f.slice_sums = ctx->d_slice_sums;
+        f.layer_ranges = st->d_fused_ranges;
+        f.n_layers = nl;
+        f.stats = layer_stats;
+        return after_launch(ctx, who, launch_fused(f, stream));
+    }
+    // Statistics of the slot's layers inside the range: one reduction per run of consecutive slot positions (a
+    // schedule in backward order gives a single run).  The first launch also carries the kernel itself.
+    bool launched = false;
+    for (int i = 0; i < nl;) {
+        if (st->layers[(size_t)i] < first || st->layers[(size_t)i] >= first + count) {
+            ++i;
+            continue;
+        }
+        int j = i + 1;
+        while (j < nl && st->layers[(size_t)j] >= first && st->layers[(size_t)j] < first + count) ++j;
+        f.slice_sums = ctx->d_slice_sums + (int64_t)i * 2 * kStatSlices;
+        f.layer_ranges = st->d_fused_ranges + 2 * i;
+        f.n_layers = j - i;
+        f.stats = layer_stats + 2 * i;
+        if (!launched) {
+            rc = launch_fused(f, stream);
+            launched = true;
+        } else {
+            rc = launch_stats(f.partials, f.slice_sums, f.layer_ranges, f.n_layers, N, f.stats, stream);
+        }
+        if (rc != 0) return after_launch(ctx, who, rc);
+        i = j;
+    }
+    if (!launched) {  // no scheduled layer in the range: plain update of these layers, no partials written
+        f.partials = nullptr;
+        rc = launch_fused(f, stream);
+    }
+    return after_launch(ctx, who, rc);
 }
 
 extern "C" int ddp_fused_sync_update(ddp_ctx *ctx, int slot, const float *const *peers, int N, int local_rank, double *layer_stats,
                                      const ddp_opt *opt, void *stream) {
-    return fused_impl(ctx, "ddp_fused_sync_update", false, slot, reinterpret_cast<const void *const *>(peers), N, local_rank, layer_stats,
-                      opt, stream);
+    return fused_impl(ctx, "ddp_fused_sync_update", false, slot, true, 0, 0, reinterpret_cast<const void *const *>(peers), N, local_rank,
+                      layer_stats, opt, stream);
 }
 
 extern "C" int ddp_fused_sync_update_wire16(ddp_ctx *ctx, int slot, const uint16_t *const *peers16, int N, int local_rank,
                                             double *layer_stats, const ddp_opt *opt, void *stream) {
-    return fused_impl(ctx, "ddp_fused_sync_update_wire16", true, slot, reinterpret_cast<const void *const *>(peers16), N, local_rank,
-                      layer_stats, opt, stream);
+    return fused_impl(ctx, "ddp_fused_sync_update_wire16", true, slot, true, 0, 0, reinterpret_cast<const void *const *>(peers16), N,
+                      local_rank, layer_stats, opt, stream);
+}
+
+extern "C" int ddp_fused_sync_update_layers(ddp_ctx *ctx, int slot, int layer_first, int layer_count, const void *const *peers,
+                                            int wire_dtype, int N, int local_rank, double *layer_stats, const ddp_opt *opt,
+                                            void *stream) {
+    if (wire_dtype != DDP_F32 && wire_dtype != DDP_BF16) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update_layers: bad wire_dtype");
+    return fused_impl(ctx, "ddp_fused_sync_update_layers", wire_dtype == DDP_BF16, slot, false, layer_first, layer_count, peers, N,
+                      local_rank, layer_stats, opt, stream);
 }

@@ -90,6 +90,11 @@ struct UpdateScalars {
 int launch_copy(bool unpack, const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, float *flat,
                 bool with_model, bool nontemporal, int lds_pad, void *stream);
 int launch_mean(const MeanLaunch &a, void *stream);
+// Per-layer statistics from per-chunk partials: layer l of n_layers adds partials [ranges[2l], ranges[2l+1]) in a fixed
+// order through kStatSlices slice sums (slice_sums: [n_layers][kStatSlices][2]) into stats[2l], stats[2l+1].
+constexpr int kStatSlices = 64;
+int launch_stats(const double *partials, double *slice_sums, const int32_t *ranges, int n_layers, int n_replicas, double *stats,
+                 void *stream);
 int launch_pack16(const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, uint16_t *flat16, bool nontemporal, int lds_pad,
                   void *stream);
 struct FusedLaunch {

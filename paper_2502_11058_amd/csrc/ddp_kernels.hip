@@ -373,8 +373,6 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
 // not hang on one workgroup: stage 1 cuts layer l's partials [ranges[2l], ranges[2l+1]) into kStatSlices contiguous
 // slices, one workgroup each (thread-strided sums, then the workgroup tree); stage 2 adds the slice sums of a layer
 // in slice order and scales the divergence by 1/N (Sec. 3.4: Gamma = 1/K sum_k ||wbar - w^k||^2, per layer).
-constexpr int kStatSlices = 64;
-
 __global__ __launch_bounds__(kThreads) void stats_slices_kernel(const double *__restrict__ partials,
                                                                 const int32_t *__restrict__ ranges, double *__restrict__ slice_sums) {
     __shared__ double lds[2][kThreads / kWave];
@@ -778,17 +776,6 @@ int launch(K kernel, int64_t grid, void *stream, int lds_pad, Args... args) {
     return (int)hipGetLastError();
 }
 
-int launch_stats(const double *partials, double *slice_sums, const int32_t *ranges, int n_layers, int n_replicas, double *stats,
-                 void *stream) {
-    if (n_layers <= 0) return 0;
-    hipLaunchKernelGGL(stats_slices_kernel, dim3(kStatSlices, (unsigned)n_layers), dim3(kThreads), 0, (hipStream_t)stream, partials,
-                       ranges, slice_sums);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return (int)e;
-    hipLaunchKernelGGL(stats_finalize_kernel, dim3((unsigned)n_layers), dim3(kWave), 0, (hipStream_t)stream,
-                       (const double *)slice_sums, n_replicas, stats);
-    return (int)hipGetLastError();
-}
 
 template <int NREP>
 int launch_mean16_n(const MeanArgs &ma, const MeanLaunch &a, void *stream) {
@@ -803,6 +790,18 @@ int launch_mean_n(const MeanArgs &ma, const MeanLaunch &a, void *stream) {
 }
 
 }  // namespace
+
+int launch_stats(const double *partials, double *slice_sums, const int32_t *ranges, int n_layers, int n_replicas, double *stats,
+                 void *stream) {
+    if (n_layers <= 0) return 0;
+    hipLaunchKernelGGL(stats_slices_kernel, dim3(kStatSlices, (unsigned)n_layers), dim3(kThreads), 0, (hipStream_t)stream, partials,
+                       ranges, slice_sums);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+    hipLaunchKernelGGL(stats_finalize_kernel, dim3((unsigned)n_layers), dim3(kWave), 0, (hipStream_t)stream,
+                       (const double *)slice_sums, n_replicas, stats);
+    return (int)hipGetLastError();
+}
 
 int launch_copy(bool unpack, const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, float *flat, bool with_model,
                 bool nontemporal, int lds_pad, void *stream) {

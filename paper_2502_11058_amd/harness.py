@@ -170,6 +170,13 @@ class DeviceReplica:
         for i in range(len(w.tensors)):
             W.normal_(self.grad[i], w.sigma_grad, W.seed_for(w.base_seed, w.name, "grad", iteration, worker, i))
 
+    def fill_grads_layer(self, iteration: int, layer: int, worker: int = 0) -> None:
+        """The draws of fill_grads for the tensors of one layer (what a backward hook of that layer would leave)."""
+        w = self.w
+        for i in range(len(w.tensors)):
+            if self.layer_of[i] == layer:
+                W.normal_(self.grad[i], w.sigma_grad, W.seed_for(w.base_seed, w.name, "grad", iteration, worker, i))
+
     def fill_peers_from(self, base_flat: torch.Tensor, iteration: int, n: int) -> None:
         """peer k = base_flat[:n] + N(0, sigma_drift), a fresh seeded draw per (iteration, peer)."""
         w = self.w
@@ -216,6 +223,31 @@ class DeviceReplica:
             return
         self.ctx.ddp_fused_sync_update(slot, self.peers, len(self.peers) + 1, local_rank, self.stats if with_stats else None,
                                        self.opt_struct(r + 1), stream)
+
+    def layerwise_step(self, r: int, side_stream, backward=None, bucket: int = 1, local_rank: int = 0, with_stats: bool = True,
+                       wire16: bool = False) -> None:
+        """Iteration r the way Sec. 3.2 overlaps it: backward(l) runs on the current stream for l = L-1 .. 0 and ends
+        with layer l's gradient written (default: the seeded draw); after every `bucket` layers an event is recorded,
+        the side stream waits for it and takes the fused sync + update of exactly those layers, so it runs under the
+        backward pass of the layers below.  The current stream finally waits for the side stream."""
+        slot = r % len(self.sets)
+        main = torch.cuda.current_stream()
+        backward = backward or (lambda l: self.fill_grads_layer(r, l))
+        peers = self.peers16 if wire16 else self.peers
+        opt = self.opt_struct(r + 1)
+        side_stream.wait_stream(main)          # everything already queued (peers, statistics buffer) is visible to the side stream
+        hi = self.w.n_layers
+        while hi > 0:
+            lo = max(0, hi - bucket)
+            for l in range(hi - 1, lo - 1, -1):
+                backward(l)
+            ready = torch.cuda.Event()
+            ready.record(main)
+            side_stream.wait_event(ready)
+            self.ctx.ddp_fused_sync_update_layers(slot, lo, hi - lo, peers, B.DDP_BF16 if wire16 else B.DDP_F32, len(peers) + 1,
+                                                  local_rank, self.stats if with_stats else None, opt, side_stream)
+            hi = lo
+        main.wait_stream(side_stream)
 
     def close(self) -> None:
         self.ctx.close()
