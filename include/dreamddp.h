@@ -235,6 +235,12 @@ int ddp_fused_sync_update_wire16(ddp_ctx *ctx, int slot, const uint16_t *const *
  *                               slot schedules are averaged and updated, the others updated.  layer_stats has the layout of
  *                               the whole-slot call (two doubles per layer of the slot, flat order); only the entries of
  *                               scheduled layers inside the range are written.
+ *                               order DDP_SYNC_THEN_UPDATE: average, then the optimizer step on the average (what the
+ *                               whole-model fused calls do).  order DDP_UPDATE_THEN_SYNC: Eq. (5) / Algorithm 1 as printed:
+ *                               the local value takes the optimizer step first and the result is averaged with the
+ *                               peers' buffers (which then hold the peers' values after their step); bit-identical to
+ *                               ddp_local_update -> ddp_pack[_wire16] -> ddp_partial_average[_wire16] -> ddp_unpack, and
+ *                               the statistics are those of that average.
  *
  * Calling either for a partition of [0, L) into ranges, once each, in any order, gives bit for bit the result of the
  * whole-model call.  Calls for disjoint ranges may be in flight at the same time on different streams of the device
@@ -242,8 +248,10 @@ int ddp_fused_sync_update_wire16(ddp_ctx *ctx, int slot, const uint16_t *const *
  * of the range's gradients and this call (stream order or an event).  Needs option dispatch_ways = 1 (the default),
  * else DDP_ESTATE.  A range with layer_count == 0 is a no-op. */
 int ddp_local_update_layers(ddp_ctx *ctx, int layer_first, int layer_count, const ddp_opt *opt, void *stream);
+enum { DDP_SYNC_THEN_UPDATE = 0, DDP_UPDATE_THEN_SYNC = 1 };
 int ddp_fused_sync_update_layers(ddp_ctx *ctx, int slot, int layer_first, int layer_count, const void *const *peers,
-                                 int wire_dtype, int N, int local_rank, double *layer_stats, const ddp_opt *opt, void *stream);
+                                 int wire_dtype, int order, int N, int local_rank, double *layer_stats, const ddp_opt *opt,
+                                 void *stream);
 
 /* Message of the last failure on this context (ctx == NULL: last failure of ddp_create / ddp_schedule* in
  * this thread).  Never NULL; valid until the next call on the same context / thread. */

@@ -16,6 +16,7 @@ LIB_PATH = os.environ.get("DREAMDDP_LIB") or os.path.join(_HERE, "lib", "libdrea
 
 DDP_F32, DDP_BF16 = 0, 1
 DDP_OPT_SGDM, DDP_OPT_ADAMW = 0, 1
+DDP_SYNC_THEN_UPDATE, DDP_UPDATE_THEN_SYNC = 0, 1
 DDP_MAX_REPLICAS = 64
 POLICIES = {"enp": 0, "round_robin": 1, "full": 2, "every": 3, "opt": 4, "alg2": 5}
 STATUS = {0: "DDP_OK", 1: "DDP_EINVAL", 2: "DDP_ESHAPE", 3: "DDP_EALIGN", 4: "DDP_ENOMEM", 5: "DDP_EHIP", 6: "DDP_ESCHED",
@@ -75,7 +76,7 @@ def lib():
         l.ddp_partial_average_wire16.argtypes = l.ddp_partial_average.argtypes
         l.ddp_fused_sync_update_wire16.argtypes = l.ddp_fused_sync_update.argtypes
         l.ddp_local_update_layers.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(ddp_opt), C.c_void_p]
-        l.ddp_fused_sync_update_layers.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int,
+        l.ddp_fused_sync_update_layers.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
                                                    C.c_void_p, C.POINTER(ddp_opt), C.c_void_p]
         l.ddp_schedule.argtypes = [C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7
         l.ddp_schedule_cost.argtypes = [C.c_int, C.c_int] + [C.c_void_p] * 5
@@ -303,11 +304,11 @@ class Context:
     def ddp_local_update_layers(self, layer_first: int, layer_count: int, opt: ddp_opt, stream=None) -> None:
         _check(lib().ddp_local_update_layers(self._h, layer_first, layer_count, C.byref(opt), _stream_handle(stream)), self._h)
 
-    def ddp_fused_sync_update_layers(self, slot: int, layer_first: int, layer_count: int, peers, wire_dtype: int, N: int,
+    def ddp_fused_sync_update_layers(self, slot: int, layer_first: int, layer_count: int, peers, wire_dtype: int, order: int, N: int,
                                      local_rank: int, layer_stats, opt: ddp_opt, stream=None) -> None:
         arr = _dev_ptrs(list(peers)) if peers else None
         _check(lib().ddp_fused_sync_update_layers(self._h, slot, layer_first, layer_count, None if arr is None else C.addressof(arr),
-                                                  wire_dtype, N, local_rank,
+                                                  wire_dtype, order, N, local_rank,
                                                   None if layer_stats is None else layer_stats.data_ptr(), C.byref(opt),
                                                   _stream_handle(stream)), self._h)
 

@@ -577,8 +577,8 @@ extern "C" int ddp_local_update_layers(ddp_ctx *ctx, int layer_first, int layer_
 
 // whole: every layer (any dispatch order).  Otherwise layers [first, first + count) only: their chunks of the update
 // table, and the statistics of those of the slot's layers that fall in the range.
-static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, bool whole, int first, int count, const void *const *peers,
-                      int N, int local_rank, double *layer_stats, const ddp_opt *opt, void *stream) {
+static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, bool update_first, int slot, bool whole, int first, int count,
+                      const void *const *peers, int N, int local_rank, double *layer_stats, const ddp_opt *opt, void *stream) {
     int rc;
     const std::string w(who);
     const SlotTables *st = slot_of(ctx, slot, who, &rc);
@@ -602,6 +602,7 @@ static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, bool
     }
     if (c1 == c0) return DDP_OK;
     f.wire16 = wire16;
+    f.update_first = update_first;
     f.n_replicas = N;
     f.local_rank = local_rank;
     f.inv_n = 1.0f / (float)N;
@@ -658,20 +659,21 @@ static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, bool
 
 extern "C" int ddp_fused_sync_update(ddp_ctx *ctx, int slot, const float *const *peers, int N, int local_rank, double *layer_stats,
                                      const ddp_opt *opt, void *stream) {
-    return fused_impl(ctx, "ddp_fused_sync_update", false, slot, true, 0, 0, reinterpret_cast<const void *const *>(peers), N, local_rank,
+    return fused_impl(ctx, "ddp_fused_sync_update", false, false, slot, true, 0, 0, reinterpret_cast<const void *const *>(peers), N, local_rank,
                       layer_stats, opt, stream);
 }
 
 extern "C" int ddp_fused_sync_update_wire16(ddp_ctx *ctx, int slot, const uint16_t *const *peers16, int N, int local_rank,
                                             double *layer_stats, const ddp_opt *opt, void *stream) {
-    return fused_impl(ctx, "ddp_fused_sync_update_wire16", true, slot, true, 0, 0, reinterpret_cast<const void *const *>(peers16), N,
+    return fused_impl(ctx, "ddp_fused_sync_update_wire16", true, false, slot, true, 0, 0, reinterpret_cast<const void *const *>(peers16), N,
                       local_rank, layer_stats, opt, stream);
 }
 
 extern "C" int ddp_fused_sync_update_layers(ddp_ctx *ctx, int slot, int layer_first, int layer_count, const void *const *peers,
-                                            int wire_dtype, int N, int local_rank, double *layer_stats, const ddp_opt *opt,
+                                            int wire_dtype, int order, int N, int local_rank, double *layer_stats, const ddp_opt *opt,
                                             void *stream) {
     if (wire_dtype != DDP_F32 && wire_dtype != DDP_BF16) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update_layers: bad wire_dtype");
-    return fused_impl(ctx, "ddp_fused_sync_update_layers", wire_dtype == DDP_BF16, slot, false, layer_first, layer_count, peers, N,
-                      local_rank, layer_stats, opt, stream);
+    if (order != DDP_SYNC_THEN_UPDATE && order != DDP_UPDATE_THEN_SYNC) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update_layers: bad order");
+    return fused_impl(ctx, "ddp_fused_sync_update_layers", wire_dtype == DDP_BF16, order == DDP_UPDATE_THEN_SYNC, slot, false, layer_first,
+                      layer_count, peers, N, local_rank, layer_stats, opt, stream);
 }

@@ -100,6 +100,7 @@ int launch_pack16(const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_
 struct FusedLaunch {
     const void *x[DDP_MAX_REPLICAS];  // peers in rank order (entry local_rank unused); fp32, or bf16 when wire16
     bool wire16;
+    bool update_first;  // Eq. (5) as printed: the local value takes the optimizer step before it is averaged
     int n_replicas, local_rank;
     float inv_n;
     int kind, grad_dtype;

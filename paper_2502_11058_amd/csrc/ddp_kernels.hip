@@ -581,12 +581,16 @@ struct FusedArgs {
     int chunk_elems;
 };
 
-// Both cases of Eq. (5) in one pass.  For a chunk of a scheduled tensor the parameter is first replaced by the
-// average over the N replicas (local values straight from the tensor, peers from their flat buffers at the
-// tensor's flat offset; same rank-ordered fp32 sum and 1/N multiply as mean_kernel), then updated; every other
-// chunk is updated only.  Result: the bits that pack -> partial average -> unpack -> local update produce, without
-// the flat round trips.  NREP > 0: replica count known at compile time; 0: run-time loop.
-template <bool ADAM, bool GBF16, bool MODEL, int NREP, bool STATS, bool W16 = false>
+// Both cases of Eq. (5) in one pass.  For a chunk of a scheduled tensor the average over the N replicas is formed from
+// the local tensor and the peers' flat buffers (read at the tensor's flat offset; same rank-ordered fp32 sum and 1/N
+// multiply as mean_kernel) and the optimizer step is applied; every other chunk gets the optimizer step only.
+//   UTS = false: average, then update the average (the bits of pack -> partial average -> unpack -> local update);
+//   UTS = true:  update the local value, then average it with the peers (Eq. (5) and Algorithm 1 as printed: the
+//                replicas that are averaged have taken this iteration's step; the bits of local update -> pack ->
+//                partial average -> unpack).
+// W16: peers are bf16 and the local replica contributes its bf16 rounding.  NREP > 0: replica count known at compile
+// time; 0: run-time loop.
+template <bool ADAM, bool GBF16, bool MODEL, int NREP, bool STATS, bool W16 = false, bool UTS = false>
 __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
     typedef GradVec<GBF16> G;
     typedef typename G::elem gelem;
@@ -614,36 +618,37 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
     const float inv_n = a.inv_n;
     double gsum = 0.0, msum = 0.0;
 
-    // replica k's value at chunk element i / group of four v (after the head h): the tensor itself for the local rank
-    // (rounded to bf16 first if that is what the peers received from this worker), else the peer's flat buffer
-    auto rep1 = [&](int k, int i) -> float {
-        if (k == lr) return W16 ? bf16_widen(bf16_rne(p[i])) : p[i];
-        return wire1<W16>(a.x[k], fo + i);
+    auto step1 = [&](float gi, float &x, float &av, float &bv) {
+        if constexpr (ADAM)
+            adamw_one(gi, x, av, bv, s);
+        else
+            sgdm_one(gi, x, av, s);
     };
 
+    // one element: scalar head and tail, and chunks whose streams are not mutually aligned
     auto one = [&](int i) {
-        float acc = rep1(0, i);
-        for (int k = 1; k < nrep; ++k) acc = acc + rep1(k, i);
+        float pl = p[i], av = s0[i], bv = ADAM ? s1[i] : 0.0f;
+        const float gi = G::widen1(g[i]);
+        if constexpr (UTS) step1(gi, pl, av, bv);
+        // what this worker contributes: its value, rounded to bf16 first if that is what its peers received
+        const float loc = W16 ? bf16_widen(bf16_rne(pl)) : pl;
+        auto term = [&](int k) -> float { return k == lr ? loc : wire1<W16>(a.x[k], fo + i); };
+        float acc = term(0);
+        for (int k = 1; k < nrep; ++k) acc = acc + term(k);
         const float m = acc * inv_n;
         if constexpr (STATS) {
             for (int k = 0; k < nrep; ++k) {
-                const float d = m - rep1(k, i);
+                const float d = m - term(k);
                 gsum += (double)d * (double)d;
             }
             msum += (double)m * (double)m;
         }
-        float pi = m, av = s0[i];
-        const float gi = G::widen1(g[i]);
-        if constexpr (ADAM) {
-            float bv = s1[i];
-            adamw_one(gi, pi, av, bv, s);
-            s1[i] = bv;
-        } else {
-            sgdm_one(gi, pi, av, s);
-        }
-        p[i] = pi;
+        float res = m;
+        if constexpr (!UTS) step1(gi, res, av, bv);
+        p[i] = res;
         s0[i] = av;
-        if constexpr (MODEL) mdl[i] = bf16_rne(pi);
+        if constexpr (ADAM) s1[i] = bv;
+        if constexpr (MODEL) mdl[i] = bf16_rne(res);
     };
 
     const int h = head_to_16B(p, n);
@@ -663,6 +668,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
         f32x4 *b4 = reinterpret_cast<f32x4 *>(s1 + h);
         const gvec *g4 = reinterpret_cast<const gvec *>(g + h);
         u16x4 *m4 = reinterpret_cast<u16x4 *>(mdl + h);
+        const int64_t vfo = (fo + h) >> 2;  // peers' index of the body's first group of four
         auto stats4 = [&](f32x4 m, f32x4 x) {
             const f32x4 d = m - x;
             gsum += (double)d.x * (double)d.x;
@@ -670,88 +676,84 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
             gsum += (double)d.z * (double)d.z;
             gsum += (double)d.w * (double)d.w;
         };
-        auto finish = [&](int v, f32x4 m, gvec gv, f32x4 av, f32x4 bv) {
-            if constexpr (STATS) {
-                msum += (double)m.x * (double)m.x;
-                msum += (double)m.y * (double)m.y;
-                msum += (double)m.z * (double)m.z;
-                msum += (double)m.w * (double)m.w;
-            }
+        auto msq4 = [&](f32x4 m) {
+            msum += (double)m.x * (double)m.x;
+            msum += (double)m.y * (double)m.y;
+            msum += (double)m.z * (double)m.z;
+            msum += (double)m.w * (double)m.w;
+        };
+        auto step4 = [&](gvec gv, f32x4 &x, f32x4 &av, f32x4 &bv) {
             const f32x4 gw = G::widen(gv);
             float G4[4] = {gw.x, gw.y, gw.z, gw.w};
-            float P4[4] = {m.x, m.y, m.z, m.w};
+            float P4[4] = {x.x, x.y, x.z, x.w};
             float A4[4] = {av.x, av.y, av.z, av.w};
             float B4[4] = {bv.x, bv.y, bv.z, bv.w};
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if constexpr (ADAM)
-                    adamw_one(G4[j], P4[j], A4[j], B4[j], s);
-                else
-                    sgdm_one(G4[j], P4[j], A4[j], s);
-            }
-            const f32x4 pn{P4[0], P4[1], P4[2], P4[3]};
-            st<NT>(p4 + v, pn);
-            st<NT>(a4 + v, f32x4{A4[0], A4[1], A4[2], A4[3]});
-            if constexpr (ADAM) st<NT>(b4 + v, f32x4{B4[0], B4[1], B4[2], B4[3]});
-            if constexpr (MODEL) st<NT>(m4 + v, bf16_rne4(pn));
+            for (int j = 0; j < 4; ++j) step1(G4[j], P4[j], A4[j], B4[j]);
+            x = f32x4{P4[0], P4[1], P4[2], P4[3]};
+            av = f32x4{A4[0], A4[1], A4[2], A4[3]};
+            bv = f32x4{B4[0], B4[1], B4[2], B4[3]};
         };
-        const int64_t vfo = (fo + h) >> 2;  // peers' index of the body's first group of four
-        auto rep4 = [&](int k, int v) -> f32x4 {
-            if constexpr (W16) {
-                if (k == lr) return bf16_widen4(bf16_rne4(ld<NT>(p4 + v)));
-                return wire4<true, NT>(a.x[k], vfo + v);
-            } else {  // same element type on both sides: select the base pointer, one load either way
-                const f32x4 *b = k == lr ? p4 : reinterpret_cast<const f32x4 *>(a.x[k]) + vfo;
-                return ld<NT>(b + v);
-            }
+        auto store4 = [&](int v, f32x4 res, f32x4 av, f32x4 bv) {
+            st<NT>(p4 + v, res);
+            st<NT>(a4 + v, av);
+            if constexpr (ADAM) st<NT>(b4 + v, bv);
+            if constexpr (MODEL) st<NT>(m4 + v, bf16_rne4(res));
         };
-        if constexpr (NREP > 0) {
+        if constexpr (NREP > 1) {
+            // The local contribution may be computed (updated and / or rounded) and a branch per replica would
+            // serialise the loads: load the N-1 peers unconditionally, all in flight before the first use, then put
+            // the local value at position lr with register selects (lr is wave-uniform).
             for (int v = tid; v < nv; v += kThreads) {
-                f32x4 x[NREP];
-                if constexpr (W16 && NREP > 1) {
-                    // The local replica has another element type than the peers, so a pointer select cannot cover
-                    // it, and a branch per replica would serialise the loads.  Load the N-1 peers unconditionally,
-                    // then put the local value at position lr with register selects (lr is wave-uniform).
-                    f32x4 pv[NREP - 1];
+                f32x4 pv[NREP - 1];
 #pragma unroll
-                    for (int j = 0; j < NREP - 1; ++j) pv[j] = wire4<true, NT>(a.x[j + (j >= lr ? 1 : 0)], vfo + v);
-                    const f32x4 loc = bf16_widen4(bf16_rne4(ld<NT>(p4 + v)));
-#pragma unroll
-                    for (int k = 0; k < NREP; ++k) {
-                        const f32x4 before = pv[k < NREP - 1 ? k : NREP - 2], after = pv[k > 0 ? k - 1 : 0];
-                        x[k] = k == lr ? loc : (k < lr ? before : after);
-                    }
-                } else {
-#pragma unroll
-                    for (int k = 0; k < NREP; ++k) x[k] = rep4(k, v);
-                }
+                for (int j = 0; j < NREP - 1; ++j) pv[j] = wire4<W16, NT>(a.x[j + (j >= lr ? 1 : 0)], vfo + v);
+                f32x4 pl = ld<NT>(p4 + v);
                 const gvec gv = ld<NT>(g4 + v);
-                const f32x4 av = ld<NT>(a4 + v);
+                f32x4 av = ld<NT>(a4 + v);
                 f32x4 bv{};
                 if constexpr (ADAM) bv = ld<NT>(b4 + v);
+                if constexpr (UTS) step4(gv, pl, av, bv);
+                f32x4 loc = pl;
+                if constexpr (W16) loc = bf16_widen4(bf16_rne4(pl));
+                f32x4 x[NREP];
+#pragma unroll
+                for (int k = 0; k < NREP; ++k) {
+                    const f32x4 before = pv[k < NREP - 1 ? k : NREP - 2], after = pv[k > 0 ? k - 1 : 0];
+                    x[k] = k == lr ? loc : (k < lr ? before : after);
+                }
                 f32x4 acc = x[0];
 #pragma unroll
                 for (int k = 1; k < NREP; ++k) acc = acc + x[k];
-                const f32x4 m = acc * inv_n;
+                f32x4 m = acc * inv_n;
                 if constexpr (STATS) {
 #pragma unroll
                     for (int k = 0; k < NREP; ++k) stats4(m, x[k]);
+                    msq4(m);
                 }
-                finish(v, m, gv, av, bv);
+                if constexpr (!UTS) step4(gv, m, av, bv);
+                store4(v, m, av, bv);
             }
         } else {
             for (int v = tid; v < nv; v += kThreads) {
-                f32x4 acc = rep4(0, v);
-                for (int k = 1; k < nrep; ++k) acc = acc + rep4(k, v);
-                const f32x4 m = acc * inv_n;
-                if constexpr (STATS) {
-                    for (int k = 0; k < nrep; ++k) stats4(m, rep4(k, v));
-                }
+                f32x4 pl = ld<NT>(p4 + v);
                 const gvec gv = ld<NT>(g4 + v);
-                const f32x4 av = ld<NT>(a4 + v);
+                f32x4 av = ld<NT>(a4 + v);
                 f32x4 bv{};
                 if constexpr (ADAM) bv = ld<NT>(b4 + v);
-                finish(v, m, gv, av, bv);
+                if constexpr (UTS) step4(gv, pl, av, bv);
+                f32x4 loc = pl;
+                if constexpr (W16) loc = bf16_widen4(bf16_rne4(pl));
+                auto term = [&](int k) -> f32x4 { return k == lr ? loc : wire4<W16, NT>(a.x[k], vfo + v); };
+                f32x4 acc = term(0);
+                for (int k = 1; k < nrep; ++k) acc = acc + term(k);
+                f32x4 m = acc * inv_n;
+                if constexpr (STATS) {
+                    for (int k = 0; k < nrep; ++k) stats4(m, term(k));
+                    msq4(m);
+                }
+                if constexpr (!UTS) step4(gv, m, av, bv);
+                store4(v, m, av, bv);
             }
         }
     }
@@ -872,22 +874,29 @@ int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *t
     return (int)hipErrorInvalidValue;
 }
 
+template <bool A, bool G, bool M, int NR>
+static int launch_fused_n(const FusedLaunch &f, const FusedArgs &fa, void *stream) {
+    const bool st = f.partials != nullptr;
+#define DDP_FUSED(W, U)                                                                                \
+    return st ? launch(fused_kernel<A, G, M, NR, true, W, U>, f.n_chunks, stream, f.lds_pad, fa)       \
+              : launch(fused_kernel<A, G, M, NR, false, W, U>, f.n_chunks, stream, f.lds_pad, fa);
+    if (f.wire16) {
+        if (f.update_first) { DDP_FUSED(true, true) }
+        DDP_FUSED(true, false)
+    }
+    if (f.update_first) { DDP_FUSED(false, true) }
+    DDP_FUSED(false, false)
+#undef DDP_FUSED
+}
+
 template <bool A, bool G, bool M>
 static int launch_fused_t(const FusedLaunch &f, const FusedArgs &fa, void *stream) {
-    const bool st = f.partials != nullptr;
-#define DDP_FUSED(NR)                                                                                                       \
-    if (f.wire16)                                                                                                           \
-        return st ? launch(fused_kernel<A, G, M, NR, true, true>, f.n_chunks, stream, f.lds_pad, fa)                        \
-                  : launch(fused_kernel<A, G, M, NR, false, true>, f.n_chunks, stream, f.lds_pad, fa);                      \
-    return st ? launch(fused_kernel<A, G, M, NR, true, false>, f.n_chunks, stream, f.lds_pad, fa)                           \
-              : launch(fused_kernel<A, G, M, NR, false, false>, f.n_chunks, stream, f.lds_pad, fa);
     switch (f.n_replicas) {
-        case 4: DDP_FUSED(4)
-        case 8: DDP_FUSED(8)
-        case 16: DDP_FUSED(16)
-        default: DDP_FUSED(0)
+        case 4: return launch_fused_n<A, G, M, 4>(f, fa, stream);
+        case 8: return launch_fused_n<A, G, M, 8>(f, fa, stream);
+        case 16: return launch_fused_n<A, G, M, 16>(f, fa, stream);
+        default: return launch_fused_n<A, G, M, 0>(f, fa, stream);
     }
-#undef DDP_FUSED
 }
 
 int launch_fused(const FusedLaunch &f, void *stream) {

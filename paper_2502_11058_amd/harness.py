@@ -214,9 +214,16 @@ class DeviceReplica:
         c.ddp_unpack(slot, self.flat, stream)
         c.ddp_local_update(self.opt_struct(r + 1), stream)
 
-    def fused_step(self, r: int, local_rank: int = 0, with_stats: bool = True, stream=None, wire16: bool = False) -> None:
+    def fused_step(self, r: int, local_rank: int = 0, with_stats: bool = True, stream=None, wire16: bool = False,
+                   order: int = B.DDP_SYNC_THEN_UPDATE) -> None:
         """Iteration r through the fused entry point: same result, no flat round trip for the local replica."""
         slot = r % len(self.sets)
+        if order != B.DDP_SYNC_THEN_UPDATE:
+            peers = self.peers16 if wire16 else self.peers
+            self.ctx.ddp_fused_sync_update_layers(slot, 0, self.w.n_layers, peers, B.DDP_BF16 if wire16 else B.DDP_F32, order,
+                                                  len(peers) + 1, local_rank, self.stats if with_stats else None,
+                                                  self.opt_struct(r + 1), stream)
+            return
         if wire16:
             self.ctx.ddp_fused_sync_update_wire16(slot, self.peers16, len(self.peers16) + 1, local_rank,
                                                   self.stats if with_stats else None, self.opt_struct(r + 1), stream)
@@ -225,7 +232,7 @@ class DeviceReplica:
                                        self.opt_struct(r + 1), stream)
 
     def layerwise_step(self, r: int, side_stream, backward=None, bucket: int = 1, local_rank: int = 0, with_stats: bool = True,
-                       wire16: bool = False) -> None:
+                       wire16: bool = False, order: int = B.DDP_SYNC_THEN_UPDATE) -> None:
         """Iteration r the way Sec. 3.2 overlaps it: backward(l) runs on the current stream for l = L-1 .. 0 and ends
         with layer l's gradient written (default: the seeded draw); after every `bucket` layers an event is recorded,
         the side stream waits for it and takes the fused sync + update of exactly those layers, so it runs under the
@@ -244,7 +251,7 @@ class DeviceReplica:
             ready = torch.cuda.Event()
             ready.record(main)
             side_stream.wait_event(ready)
-            self.ctx.ddp_fused_sync_update_layers(slot, lo, hi - lo, peers, B.DDP_BF16 if wire16 else B.DDP_F32, len(peers) + 1,
+            self.ctx.ddp_fused_sync_update_layers(slot, lo, hi - lo, peers, B.DDP_BF16 if wire16 else B.DDP_F32, order, len(peers) + 1,
                                                   local_rank, self.stats if with_stats else None, opt, side_stream)
             hi = lo
         main.wait_stream(side_stream)

@@ -119,7 +119,7 @@ def run_trajectory(oracle, w, policy=None, iters=None, arena_offset=0, options=N
     for r in range(iters):
         slot, S = r % H, sets[r % H]
         rank = r % N
-        if order == 1:
+        if order == 1 and not fused:
             update_both(r)
         # layout: offsets, tensor ids, layer ids
         off, order_t, total = oracle.slot_offsets(rep.layer_of, rep.numel, S)
@@ -149,7 +149,7 @@ def run_trajectory(oracle, w, policy=None, iters=None, arena_offset=0, options=N
                 def backward(l):
                     busy.copy_(busy @ busy_w)
                     rep.fill_grads_layer(r, l)
-                rep.layerwise_step(r, side, backward=backward, bucket=layerwise, local_rank=rank, wire16=wire16)
+                rep.layerwise_step(r, side, backward=backward, bucket=layerwise, local_rank=rank, wire16=wire16, order=order)
                 torch.cuda.synchronize()
                 grads = [_np(g) for g in rep.grad]
             else:
@@ -157,20 +157,27 @@ def run_trajectory(oracle, w, policy=None, iters=None, arena_offset=0, options=N
                 grads = [_np(g) for g in rep.grad]
             if layerwise:
                 pass
+            elif order == 1:
+                rep.fused_step(r, rank, wire16=wire16, order=1)
             elif wire16:
                 rep.ctx.ddp_fused_sync_update_wire16(slot, rep.peers16, N, rank, rep.stats, rep.opt_struct(r + 1))
             else:
                 rep.ctx.ddp_fused_sync_update(slot, rep.peers, N, rank, rep.stats, rep.opt_struct(r + 1))
-            reps = peers_host[:rank] + [local_host] + peers_host[rank:]
-            o_mean, o_stats = (oracle.mean_wire16, oracle.layer_stats_wire16) if wire16 else (oracle.mean, oracle.layer_stats)
-            mean_ref = o_mean(reps) if total else np.zeros(0, np.float32)
             st = _np(rep.stats)
-            for i, (b, e) in enumerate(ranges):
-                g, m = o_stats(reps, mean_ref, b, e)
+            if order == 1:
+                # Eq. (5) as printed: the carried oracle worker steps, then averages its stepped values with the peers
+                wk.local_update(grads, r + 1)
+                _, ref_stats = wk.sync(S, peers_host, rank, wire16=wire16)
+            else:
+                reps = peers_host[:rank] + [local_host] + peers_host[rank:]
+                o_mean, o_stats = (oracle.mean_wire16, oracle.layer_stats_wire16) if wire16 else (oracle.mean, oracle.layer_stats)
+                mean_ref = o_mean(reps) if total else np.zeros(0, np.float32)
+                ref_stats = [o_stats(reps, mean_ref, b, e) for (b, e) in ranges]
+                wk.sync(S, peers_host, rank, wire16=wire16)
+                wk.local_update(grads, r + 1)
+            for i, (g, m) in enumerate(ref_stats):
                 assert st[2 * i] == pytest.approx(g, rel=1e-10, abs=1e-300), f"fused gamma r={r} layer {S[i]}"
                 assert st[2 * i + 1] == pytest.approx(m, rel=1e-10), f"fused msq r={r} layer {S[i]}"
-            wk.sync(S, peers_host, rank, wire16=wire16)
-            wk.local_update(grads, r + 1)
         elif wire16:
             # bf16 on the wire: pack rounds, the average widens; every stage against the oracle on the same bytes
             dev_flat = torch.cat([rep.sync[t] for t in order_t]) if total else rep.flat[:0]
@@ -337,6 +344,25 @@ def test_layerwise_launches_on_a_side_stream_equal_the_whole_step(oracle, name, 
     assert t.frac() == 1.0
 
 
+@pytest.mark.parametrize("wire16", [False, True])
+@pytest.mark.parametrize("name,kw,layerwise", [("tiny", {}, 0), ("small_llama", {}, 0), ("small_llama", {"n_replicas": 5, "period": 3}, 2),
+                                               ("small_llama", {"n_replicas": 16}, 0), ("small_llama", {"n_replicas": 4, "period": 2}, 1)])
+def test_fused_update_then_sync_is_eq5_as_printed(oracle, name, kw, layerwise, wire16):
+    # the local value takes the optimizer step, then the stepped values are averaged (Eq. (5), Algorithm 1)
+    w = W.WORKLOADS[name](**kw)
+    t = run_trajectory(oracle, w, fused=True, order=1, wire16=wire16, layerwise=layerwise, iters=8)
+    assert t.frac() == 1.0
+
+
+@pytest.mark.parametrize("arena_offset", [0, 1, 2, 3])
+def test_fused_update_then_sync_odd_shapes(oracle, arena_offset):
+    w = W.odd(optimizer="adamw", param_dtype="bf16", n_replicas=4, period=2)
+    t = run_trajectory(oracle, w, fused=True, order=1, arena_offset=arena_offset, options={"update_chunk": 1024})
+    assert t.frac() == 1.0
+    w = W.odd(optimizer="sgdm", param_dtype="f32", n_replicas=3, period=3)
+    run_trajectory(oracle, w, fused=True, order=1, wire16=True, arena_offset=arena_offset, policy="full")
+
+
 def test_local_update_by_layer_ranges_equals_the_whole_update(oracle):
     from paper_2502_11058_amd.harness import DeviceReplica
     _need_gpu()
@@ -360,7 +386,9 @@ def test_local_update_by_layer_ranges_equals_the_whole_update(oracle):
         b.ctx.ddp_local_update_layers(L - 1, 2, b.opt_struct(4))
     assert "layer range" in str(e.value)
     with pytest.raises(Exception):
-        b.ctx.ddp_fused_sync_update_layers(0, -1, 1, b.peers, 0, w.n_replicas, 0, None, b.opt_struct(4))
+        b.ctx.ddp_fused_sync_update_layers(0, -1, 1, b.peers, 0, 0, w.n_replicas, 0, None, b.opt_struct(4))
+    with pytest.raises(Exception):
+        b.ctx.ddp_fused_sync_update_layers(0, 0, 1, b.peers, 0, 2, w.n_replicas, 0, None, b.opt_struct(4))       # bad order
     c = DeviceReplica(w, 0, options={"dispatch_ways": 4})
     with pytest.raises(Exception) as e:
         c.ctx.ddp_local_update_layers(0, 1, c.opt_struct(1))
