@@ -382,19 +382,19 @@ class Worker:
         return res
 
 
-def run_workers(workers: List[Worker], r: int, sets, grads_per_worker, order: int = SYNC_THEN_UPDATE):
+def run_workers(workers: List[Worker], r: int, sets, grads_per_worker, order: int = SYNC_THEN_UPDATE, wire16: bool = False):
     """One iteration of Algorithm 1 for K workers held in this process: each worker's peers are the other
-    workers' packed buffers of the same iteration."""
+    workers' packed buffers of the same iteration (bf16 buffers with wire16)."""
     K = len(workers)
     S = sets[r % len(sets)]
     if order == UPDATE_THEN_SYNC:
         for k in range(K):
             workers[k].local_update(grads_per_worker[k], r + 1)
-    flats = [w.pack_slot(S)[0] for w in workers]
+    flats = [w.pack_slot(S, wire16)[0] for w in workers]
     results = []
     for k in range(K):
         peers = [flats[j] for j in range(K) if j != k]
-        results.append(workers[k].sync(S, peers, k))
+        results.append(workers[k].sync(S, peers, k, wire16))
     if order == SYNC_THEN_UPDATE:
         for k in range(K):
             workers[k].local_update(grads_per_worker[k], r + 1)
