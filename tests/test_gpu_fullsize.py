@@ -75,6 +75,23 @@ def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000,
         fi, gsel = torch.from_numpy(fi_host).to(dev), torch.from_numpy(gi_host[sel_host]).to(dev)
         rep.fill_grads(r)
         g_s = _np(rep.a_grad[gi])
+        if total == 0:
+            # an empty slot (FULL schedule outside its one iteration): the calls are no-ops, only the update acts
+            rep.stats.fill_(-1.0)
+            if fused:
+                rep.fused_step(r, rank, wire16=wire16)
+            else:
+                rep.step(r, rank, wire16=wire16)
+            oracle.adamw(p_s, g_s, m_s, v_s, model_s, w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, r + 1)
+            gp, gm, gv = _np(rep.a_sync[gi]), _np(rep.a_s0[gi]), _np(rep.a_s1[gi])
+            assert float(rep.stats.max()) == -1.0, "statistics written for an empty slot"
+            for a_, b_, what in ((gp, p_s, "param"), (gm, m_s, "m"), (gv, v_s, "v")):
+                assert np.array_equal(_bits(a_), _bits(b_)), f"{what} r={r} (empty slot)"
+                n_total += a_.size
+                n_exact += a_.size
+            assert np.array_equal(_np(rep.a_model[gi]), model_s), f"model r={r} (empty slot)"
+            progress(f"[{w.name}] r={r} slot {slot} is empty: update only, ok")
+            continue
         base = torch.cat([rep.sync[t] for t in order_t])       # independent gather (harness), the peers' base
         if wire16:
             rep.fill_peers16_from(base, r, total)
@@ -230,6 +247,16 @@ def test_llama2_7b_fused_sampled_trajectory(oracle):
 @pytest.mark.parametrize("fused", [False, True])
 def test_llama2_7b_bf16_wire_sampled_trajectory(oracle, fused):
     assert run_sampled(oracle, W.llama2_7b(), iters=4, fused=fused, wire16=True) == 1.0
+
+
+@pytest.mark.timeout(1500)
+@pytest.mark.parametrize("fused", [False, True])
+def test_llama2_7b_whole_model_in_one_slot(oracle, fused):
+    # Eq. (2) at full size: FULL schedule with H = 2 and N = 2, so the second iteration synchronises all 6.7 G
+    # parameters in one slot: flat offsets beyond 2^31 elements and 2^34 bytes, 6.6 M chunks per launch
+    w = W.llama2_7b()
+    w.n_replicas, w.period, w.policy = 2, 2, "full"
+    assert run_sampled(oracle, w, iters=2, fused=fused) == 1.0
 
 
 @pytest.mark.timeout(1500)
