@@ -28,8 +28,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 
 # HBM bytes per launch of the update kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what
-# the same counters read for a plain copy of known size (profiles/llama2_7b_step_kernels.txt); None if not measured.
-MEASURED_TRAFFIC_BYTES = {"llama2_7b": 189.099e9}
+# the same counters read for a plain copy of known size (profiles/llama2_7b_step_kernels.txt); None if not measured
+# (other workloads, or library options that differ from the defaults the measurement was taken with).
+MEASURED_TRAFFIC_BYTES = {"llama2_7b": 188.681e9}
 
 
 def algorithmic_bytes(w, S: int):
@@ -213,7 +214,7 @@ def main() -> int:
     dom = "local_update"
     achieved = kernels[dom]["GB/s"]
     roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if not options else None,
                 "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"], "avg_launch_ms": kernels[dom]["avg_ms"]}
 
     # ---- pass 3: the fused entry point (both cases of Eq. (5) in one pass), K steps, wall clock --------------------

@@ -128,6 +128,10 @@ int ddp_destroy(ddp_ctx *ctx);
  *                                               keeps the window of DRAM rows in flight narrow (defaults 65536 / 53248 /
  *                                               24576 = 2 / 3 / 6 workgroups per CU)
  *   "nontemporal"                               0/1 (default 1): streaming cache hints on loads and stores
+ *   "dense_path"                                0/1 (default 1): when the registered tensors lie back to back in every
+ *                                               stream (one arena per stream, starts 16-byte aligned, bf16 streams
+ *                                               8-byte), the update addresses its data from the block index alone
+ *                                               instead of through the chunk table; 0 forces the table
  * Unknown names or bad values: DDP_EINVAL. */
 int ddp_set_option(ddp_ctx *ctx, const char *name, int64_t value);
 

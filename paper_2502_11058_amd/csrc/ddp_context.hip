@@ -47,6 +47,8 @@ static void free_slot(SlotTables &s) {
     if (s.d_layer_ranges) (void)hipFree(s.d_layer_ranges);
     if (s.d_tensor_flat_off) (void)hipFree(s.d_tensor_flat_off);
     if (s.d_fused_ranges) (void)hipFree(s.d_fused_ranges);
+    if (s.d_dense_ranges) (void)hipFree(s.d_dense_ranges);
+    s.d_dense_ranges = nullptr;
     s.d_copy = nullptr;
     s.d_mean = nullptr;
     s.d_layer_ranges = nullptr;
@@ -164,6 +166,11 @@ extern "C" int ddp_set_option(ddp_ctx *ctx, const char *name, int64_t value) {
         (k == "update_lds" ? ctx->update_lds : k == "mean_lds" ? ctx->mean_lds : ctx->copy_lds) = (int)value;
         return DDP_OK;
     }
+    if (k == "dense_path") {
+        if (value != 0 && value != 1) return fail(ctx, DDP_EINVAL, "ddp_set_option: dense_path is 0 or 1");
+        ctx->dense_path = value != 0;
+        return DDP_OK;
+    }
     if (k == "nontemporal") {
         if (value != 0 && value != 1) return fail(ctx, DDP_EINVAL, "ddp_set_option: nontemporal is 0 or 1");
         ctx->nontemporal = value != 0;
@@ -224,6 +231,20 @@ extern "C" int ddp_register_model(ddp_ctx *ctx, int L, int T, const int32_t *lay
         ctx->numel.assign(numel, numel + T);
         ctx->tensors = ts;
         ctx->layer_first_tensor = first;
+        // Dense arenas: every tensor starts where the previous one ends, in every stream, and the streams start on
+        // 128-bit (bf16: 64-bit) boundaries.  The update then needs no table.
+        ctx->tensor_elem_off.assign((size_t)T + 1, 0);
+        for (int t = 0; t < T; ++t) ctx->tensor_elem_off[(size_t)t + 1] = ctx->tensor_elem_off[(size_t)t] + numel[t];
+        const uintptr_t gsz = grad_dtype == DDP_F32 ? 4 : 2;
+        bool dense = aligned(ts[0].sync, 16) && aligned(ts[0].state0, 16) && aligned(ts[0].grad, 4 * gsz) &&
+                     (!has1 || aligned(ts[0].state1, 16)) && (param_dtype != DDP_BF16 || aligned(ts[0].model, 8));
+        for (int t = 1; t < T && dense; ++t) {
+            const TensorDesc &a = ts[(size_t)t - 1], &b = ts[(size_t)t];
+            dense = b.sync == a.sync + a.numel && b.state0 == a.state0 + a.numel && (!has1 || b.state1 == a.state1 + a.numel) &&
+                    (const char *)b.grad == (const char *)a.grad + (uintptr_t)a.numel * gsz &&
+                    (param_dtype != DDP_BF16 || b.model == a.model + a.numel);
+        }
+        ctx->dense = dense;
 
         // update table: every tensor cut into runs of update_chunk elements
         std::vector<UpdateChunk> uc;
@@ -278,6 +299,14 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
 
         drop_schedule(ctx);
         std::vector<SlotTables> slots((size_t)H);
+        // workgroups of the table-free fused kernel, layer by layer in registration order (never more than the update
+        // table has chunks, so the reduction scratch sized for the table covers them)
+        std::vector<int64_t> dense_wg_base((size_t)ctx->L + 1, 0);
+        for (int l = 0; l < ctx->L; ++l) {
+            const int64_t n = ctx->tensor_elem_off[(size_t)ctx->layer_first_tensor[(size_t)l + 1]] -
+                              ctx->tensor_elem_off[(size_t)ctx->layer_first_tensor[(size_t)l]];
+            dense_wg_base[(size_t)l + 1] = dense_wg_base[(size_t)l] + (n + ctx->update_chunk - 1) / ctx->update_chunk;
+        }
         int64_t max_mean_chunks = 0;
         for (int s = 0; s < H; ++s) {
             SlotTables &st = slots[(size_t)s];
@@ -293,6 +322,8 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
                 lcp.push_back((int32_t)mc.size());
                 fused_ranges.push_back(ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)l]]);
                 fused_ranges.push_back(ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)l + 1]]);
+                st.dense_ranges.push_back((int32_t)dense_wg_base[(size_t)l]);
+                st.dense_ranges.push_back((int32_t)dense_wg_base[(size_t)l + 1]);
                 const int64_t layer_start = off;
                 for (int t = ctx->layer_first_tensor[(size_t)l]; t < ctx->layer_first_tensor[(size_t)l + 1]; ++t) {
                     st.tensors.push_back(t);
@@ -335,6 +366,7 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
             if (rc == DDP_OK) rc = upload(ctx, mean_ranges, &st.d_layer_ranges);
             if (rc == DDP_OK) rc = upload(ctx, tflat, &st.d_tensor_flat_off);
             if (rc == DDP_OK) rc = upload(ctx, fused_ranges, &st.d_fused_ranges);
+            if (rc == DDP_OK) rc = upload(ctx, st.dense_ranges, &st.d_dense_ranges);
             if (rc != DDP_OK) {
                 for (auto &x : slots) free_slot(x);
                 return rc;
@@ -551,6 +583,24 @@ static int layer_chunk_range(ddp_ctx *ctx, const char *who, int first, int count
     return DDP_OK;
 }
 
+// The streams of layers [first, first + count) as one dense range, if the model is registered that way, the option
+// allows it and the range starts on a vector boundary.
+static bool dense_range(const ddp_ctx *ctx, int first, int count, DenseLaunch &d) {
+    if (!ctx->dense || !ctx->dense_path) return false;
+    const int64_t e0 = ctx->tensor_elem_off[(size_t)ctx->layer_first_tensor[(size_t)first]];
+    const int64_t e1 = ctx->tensor_elem_off[(size_t)ctx->layer_first_tensor[(size_t)(first + count)]];
+    if (e0 % 4 != 0) return false;
+    const TensorDesc &t0 = ctx->tensors[0];
+    d.p = t0.sync + e0;
+    d.s0 = t0.state0 + e0;
+    d.s1 = ctx->has_state1 ? t0.state1 + e0 : nullptr;
+    d.g = (const char *)t0.grad + (uintptr_t)e0 * (ctx->grad_dtype == DDP_F32 ? 4 : 2);
+    d.mdl = ctx->param_dtype == DDP_BF16 ? t0.model + e0 : nullptr;
+    d.n = e1 - e0;
+    d.chunk = (int)ctx->update_chunk;
+    return true;
+}
+
 static int local_update_impl(ddp_ctx *ctx, const char *who, bool whole, int first, int count, const ddp_opt *opt, void *stream) {
     const std::string w(who);
     if (!ctx) return fail(nullptr, DDP_EINVAL, w + ": ctx is NULL");
@@ -562,6 +612,11 @@ static int local_update_impl(ddp_ctx *ctx, const char *who, bool whole, int firs
     int64_t c0 = 0, c1 = ctx->n_update;
     if (!whole && (rc = layer_chunk_range(ctx, who, first, count, &c0, &c1)) != DDP_OK) return rc;
     if (c1 == c0) return DDP_OK;
+    DenseLaunch d{};
+    if (dense_range(ctx, whole ? 0 : first, whole ? ctx->L : count, d)) {
+        rc = launch_update_dense(opt->kind, ctx->grad_dtype, ctx->param_dtype == DDP_BF16, d, s, ctx->nontemporal, ctx->update_lds, stream);
+        return after_launch(ctx, who, rc);
+    }
     rc = launch_update(opt->kind, ctx->grad_dtype, ctx->param_dtype == DDP_BF16, ctx->d_tensors, ctx->d_update + c0, c1 - c0, s,
                        ctx->nontemporal, ctx->update_lds, stream);
     return after_launch(ctx, who, rc);
@@ -573,6 +628,73 @@ extern "C" int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream) 
 
 extern "C" int ddp_local_update_layers(ddp_ctx *ctx, int layer_first, int layer_count, const ddp_opt *opt, void *stream) {
     return local_update_impl(ctx, "ddp_local_update_layers", false, layer_first, layer_count, opt, stream);
+}
+
+// The fused step over layers [first, first + count) of a model registered as dense arenas: one table-free launch per
+// scheduled layer and one per run of unscheduled layers.  *done = false (nothing launched) when the model, the
+// options, the replica count or an alignment rule the table-free kernels out; the caller then takes the table.
+static int fused_dense(ddp_ctx *ctx, const char *who, const SlotTables *st, const void *const *x, bool wire16, bool update_first, int first,
+                       int count, int N, int local_rank, double *layer_stats, const ddp_opt *opt, const UpdateScalars &s, void *stream,
+                       bool *done) {
+    *done = false;
+    if (!ctx->dense || !ctx->dense_path || !ctx->nontemporal || !fused_dense_supports(N)) return DDP_OK;
+    std::vector<int> pos((size_t)ctx->L, -1);  // layer -> position in the slot
+    for (size_t i = 0; i < st->layers.size(); ++i) pos[(size_t)st->layers[i]] = (int)i;
+    auto elem0 = [&](int l) { return ctx->tensor_elem_off[(size_t)ctx->layer_first_tensor[(size_t)l]]; };
+    // every launch must start on a vector boundary in the model and, for a scheduled layer, in the flat buffer
+    for (int l = first; l < first + count; ++l) {
+        const bool sched = pos[(size_t)l] >= 0, run_start = l == first || sched || pos[(size_t)l - 1] >= 0;
+        if (run_start && elem0(l) % 4 != 0) return DDP_OK;
+        if (sched && ((elem0(l + 1) - elem0(l)) % 4 != 0 || st->layer_begin[(size_t)pos[(size_t)l]] % 4 != 0)) return DDP_OK;
+    }
+    *done = true;
+    const bool stats = layer_stats != nullptr;
+    int rc = 0;
+    for (int l = first; l < first + count && rc == 0;) {
+        DenseLaunch d{};
+        if (pos[(size_t)l] < 0) {
+            int m = l + 1;
+            while (m < first + count && pos[(size_t)m] < 0) ++m;
+            dense_range(ctx, l, m - l, d);
+            rc = launch_update_dense(opt->kind, ctx->grad_dtype, ctx->param_dtype == DDP_BF16, d, s, true, ctx->update_lds, stream);
+            l = m;
+            continue;
+        }
+        const int i = pos[(size_t)l];
+        FusedDenseLaunch f{};
+        dense_range(ctx, l, 1, f.d);
+        for (int k = 0; k < N; ++k) f.x[k] = x[k];
+        f.wire16 = wire16;
+        f.update_first = update_first;
+        f.n_replicas = N;
+        f.local_rank = local_rank;
+        f.inv_n = 1.0f / (float)N;
+        f.kind = opt->kind;
+        f.grad_dtype = ctx->grad_dtype;
+        f.with_model = ctx->param_dtype == DDP_BF16;
+        f.fo0 = st->layer_begin[(size_t)i];
+        f.s = s;
+        f.partials = stats ? ctx->d_partials : nullptr;
+        f.pbase = st->dense_ranges[2 * (size_t)i];
+        f.lds_pad = ctx->update_lds;
+        rc = launch_fused_dense(f, stream);
+        ++l;
+    }
+    // statistics of the slot's layers inside the range: one reduction per run of consecutive slot positions
+    const int nl = (int)st->layers.size();
+    for (int i = 0; stats && rc == 0 && i < nl;) {
+        auto inside = [&](int j) { return st->layers[(size_t)j] >= first && st->layers[(size_t)j] < first + count; };
+        if (!inside(i)) {
+            ++i;
+            continue;
+        }
+        int j = i + 1;
+        while (j < nl && inside(j)) ++j;
+        rc = launch_stats(ctx->d_partials, ctx->d_slice_sums + (int64_t)i * 2 * kStatSlices, st->d_dense_ranges + 2 * i, j - i, N,
+                          layer_stats + 2 * i, stream);
+        i = j;
+    }
+    return after_launch(ctx, who, rc);
 }
 
 // whole: every layer (any dispatch order).  Otherwise layers [first, first + count) only: their chunks of the update
@@ -601,6 +723,12 @@ static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, bool update_fi
         f.x[k] = q;
     }
     if (c1 == c0) return DDP_OK;
+    {
+        bool done = false;
+        rc = fused_dense(ctx, who, st, f.x, wire16, update_first, whole ? 0 : first, whole ? ctx->L : count, N, local_rank, layer_stats,
+                         opt, s, stream, &done);
+        if (done) return rc;
+    }
     f.wire16 = wire16;
     f.update_first = update_first;
     f.n_replicas = N;

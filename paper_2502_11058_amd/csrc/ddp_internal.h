@@ -62,6 +62,10 @@ struct SlotTables {
     int32_t *d_layer_ranges = nullptr;     // per layer of the slot: [first, last) mean chunk
     int64_t *d_tensor_flat_off = nullptr;  // per registered tensor: first flat index in this slot, -1 if unscheduled
     int32_t *d_fused_ranges = nullptr;     // per layer of the slot: [first, last) update chunk (registration order)
+    // dense arenas: per layer of the slot [first, last) index of its workgroups' partials (layers numbered in
+    // registration order, ceil(layer elements / update_chunk) workgroups each)
+    std::vector<int32_t> dense_ranges;
+    int32_t *d_dense_ranges = nullptr;
 };
 
 // ---- launchers (ddp_kernels.hip) -------------------------------------------------------------------------------
@@ -120,6 +124,36 @@ struct FusedLaunch {
     int lds_pad;
 };
 int launch_fused(const FusedLaunch &f, void *stream);
+// The update over tensors that lie back to back in every stream: the range's first element in each stream (aligned
+// for 128-bit access, bf16 streams for 64-bit), its length and the elements per workgroup.
+struct DenseLaunch {
+    const void *g;
+    float *p, *s0, *s1;
+    uint16_t *mdl;
+    int64_t n;
+    int chunk;
+};
+int launch_update_dense(int kind, int grad_dtype, bool with_model, const DenseLaunch &d, const UpdateScalars &s, bool nontemporal,
+                        int lds_pad, void *stream);
+// One scheduled layer of a dense model through the fused kernel: local streams d (d.n a multiple of 4), peers' flat
+// buffers x, the layer's first flat index fo0 (a multiple of 4); workgroup b's partial pair goes to partials[2 * (pbase + b)]
+// (nullptr: no statistics).  Replica counts fused_dense_supports() accepts only.
+struct FusedDenseLaunch {
+    DenseLaunch d;
+    const void *x[DDP_MAX_REPLICAS];
+    bool wire16, update_first;
+    int n_replicas, local_rank;
+    float inv_n;
+    int kind, grad_dtype;
+    bool with_model;
+    int64_t fo0;
+    UpdateScalars s;
+    double *partials;
+    int64_t pbase;
+    int lds_pad;
+};
+bool fused_dense_supports(int n_replicas);
+int launch_fused_dense(const FusedDenseLaunch &f, void *stream);
 int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *tensors, const UpdateChunk *chunks,
                   int64_t n_chunks, const UpdateScalars &s, bool nontemporal, int lds_pad, void *stream);
 
@@ -142,6 +176,9 @@ struct ddp_ctx {
     std::vector<int64_t> numel;
     std::vector<ddp::TensorDesc> tensors;
     std::vector<int32_t> layer_first_tensor;  // L + 1
+    std::vector<int64_t> tensor_elem_off;     // T + 1: elements before each tensor, registration order
+    bool dense = false;      // tensors lie back to back in every stream and the streams' starts are vector-aligned
+    bool dense_path = true;  // option: use the table-free kernels where `dense` allows it
     ddp::TensorDesc *d_tensors = nullptr;
     ddp::UpdateChunk *d_update = nullptr;
     int64_t n_update = 0;

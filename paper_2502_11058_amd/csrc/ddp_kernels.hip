@@ -564,8 +564,188 @@ __global__ __launch_bounds__(kThreads) void update_kernel(const TensorDesc *__re
 }
 
 // ---------------------------------------------------------------------------------------------------------------
+// local update over dense arenas
+// ---------------------------------------------------------------------------------------------------------------
+
+// Buffer (MUBUF) accesses: a per-workgroup descriptor (base in SGPRs, extent = the workgroup's part of the stream)
+// plus a 32-bit byte offset per lane.  Accesses past the extent read zero / are dropped by the hardware.
+// AUX: cache policy bits of the instruction (2 = nt, the streaming hint; 0 = default).
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, int bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);  // raw dword format
+}
+
+template <int AUX, class T>
+__device__ __forceinline__ T bld(__amdgpu_buffer_rsrc_t r, int byte_off) {
+    static_assert(sizeof(T) == 16 || sizeof(T) == 8, "128- or 64-bit access");
+    if constexpr (sizeof(T) == 16)
+        return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, AUX));
+    else
+        return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, AUX));
+}
+
+template <int AUX, class T>
+__device__ __forceinline__ void bst(__amdgpu_buffer_rsrc_t r, int byte_off, T v) {
+    static_assert(sizeof(T) == 16 || sizeof(T) == 8, "128- or 64-bit access");
+    if constexpr (sizeof(T) == 16)
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, byte_off, 0, AUX);
+    else
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), r, byte_off, 0, AUX);
+}
+
+struct DenseArgs {
+    const void *g;  // the five streams at the first element of the range, each aligned for 128-bit (bf16: 64-bit) access
+    float *p;
+    float *s0;
+    float *s1;
+    unsigned short *mdl;
+    int64_t n;  // elements in the range
+    int chunk;  // elements per workgroup, a multiple of 1024
+    UpdateScalars s;
+};
+
+// The update when the registered tensors lie back to back in every stream (one arena per stream): workgroup b takes
+// elements [b * chunk, (b + 1) * chunk) of the range, addresses follow from the block index alone (no table), and
+// every chunk starts aligned, so there is no head; only the last workgroup has a tail of fewer than four elements.
+// Same operations per element as update_kernel, hence the same bits.
+template <bool ADAM, bool GBF16, bool MODEL, int AUX>
+__global__ __launch_bounds__(kThreads) void update_dense_kernel(const DenseArgs a) {
+    typedef GradVec<GBF16> G;
+    typedef typename G::elem gelem;
+    typedef typename G::vec gvec;
+    const int64_t b = (int64_t)blockIdx.x * a.chunk;
+    const int64_t left = a.n - b;
+    const int count = left < (int64_t)a.chunk ? (int)left : a.chunk;
+    const UpdateScalars &s = a.s;
+    float *p = a.p + b;
+    float *s0 = a.s0 + b;
+    float *s1 = ADAM ? a.s1 + b : s0;
+    const gelem *g = reinterpret_cast<const gelem *>(a.g) + b;
+    unsigned short *mdl = MODEL ? a.mdl + b : reinterpret_cast<unsigned short *>(p);
+    const int tid = threadIdx.x;
+    const int nv = count >> 2;
+    const __amdgpu_buffer_rsrc_t rp = make_rsrc(p, nv * 16), ra = make_rsrc(s0, nv * 16), rb = make_rsrc(s1, nv * 16),
+                                 rg = make_rsrc(g, nv * (int)sizeof(gvec)), rm = make_rsrc(mdl, nv * 8);
+
+    auto finish = [&](int v, gvec gv, f32x4 pv, f32x4 av, f32x4 bv) {
+        const f32x4 gw = G::widen(gv);
+        float G4[4] = {gw.x, gw.y, gw.z, gw.w};
+        float P4[4] = {pv.x, pv.y, pv.z, pv.w};
+        float A4[4] = {av.x, av.y, av.z, av.w};
+        float B4[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (ADAM)
+                adamw_one(G4[j], P4[j], A4[j], B4[j], s);
+            else
+                sgdm_one(G4[j], P4[j], A4[j], s);
+        }
+        const f32x4 pn{P4[0], P4[1], P4[2], P4[3]};
+        bst<AUX>(rp, v * 16, pn);
+        bst<AUX>(ra, v * 16, f32x4{A4[0], A4[1], A4[2], A4[3]});
+        if constexpr (ADAM) bst<AUX>(rb, v * 16, f32x4{B4[0], B4[1], B4[2], B4[3]});
+        if constexpr (MODEL) bst<AUX>(rm, v * 8, bf16_rne4(pn));
+    };
+
+    int v = tid;
+    for (; v + kThreads < nv; v += 2 * kThreads) {
+        const int w = v + kThreads;
+        const gvec g0 = bld<AUX, gvec>(rg, v * (int)sizeof(gvec)), g1 = bld<AUX, gvec>(rg, w * (int)sizeof(gvec));
+        const f32x4 p0 = bld<AUX, f32x4>(rp, v * 16), p1 = bld<AUX, f32x4>(rp, w * 16);
+        const f32x4 a0 = bld<AUX, f32x4>(ra, v * 16), a1 = bld<AUX, f32x4>(ra, w * 16);
+        f32x4 b0{}, b1{};
+        if constexpr (ADAM) {
+            b0 = bld<AUX, f32x4>(rb, v * 16);
+            b1 = bld<AUX, f32x4>(rb, w * 16);
+        }
+        finish(v, g0, p0, a0, b0);
+        finish(w, g1, p1, a1, b1);
+    }
+    for (; v < nv; v += kThreads) {
+        const gvec g0 = bld<AUX, gvec>(rg, v * (int)sizeof(gvec));
+        const f32x4 p0 = bld<AUX, f32x4>(rp, v * 16);
+        const f32x4 a0 = bld<AUX, f32x4>(ra, v * 16);
+        f32x4 b0{};
+        if constexpr (ADAM) b0 = bld<AUX, f32x4>(rb, v * 16);
+        finish(v, g0, p0, a0, b0);
+    }
+    const int i = 4 * nv + tid;  // fewer than four elements, last workgroup of the range only
+    if (i < count) {
+        float pi = p[i], av = s0[i];
+        const float gi = G::widen1(g[i]);
+        if constexpr (ADAM) {
+            float bv = s1[i];
+            adamw_one(gi, pi, av, bv, s);
+            s1[i] = bv;
+        } else {
+            sgdm_one(gi, pi, av, s);
+        }
+        p[i] = pi;
+        s0[i] = av;
+        if constexpr (MODEL) mdl[i] = bf16_rne(pi);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
 // fused synchronisation + update
 // ---------------------------------------------------------------------------------------------------------------
+
+// One group of four elements of a scheduled tensor, N known at compile time: pv = the N-1 peers' values (rank order,
+// local rank left out), x = the local parameter on entry and the value to store on return, av / bv = optimizer state
+// (updated in place).  The local contribution (x, stepped first if UTS, rounded to bf16 if W16) is put at position
+// lr with register selects (lr is wave-uniform); rank-order fp32 sum, one multiply by 1/N; statistics in fp64.
+template <bool ADAM, bool GBF16, int NREP, bool STATS, bool W16, bool UTS>
+__device__ __forceinline__ void fused_math4(const f32x4 (&pv)[NREP - 1], typename GradVec<GBF16>::vec gv, f32x4 &x, f32x4 &av, f32x4 &bv,
+                                            int lr, float inv_n, const UpdateScalars &s, double &gsum, double &msum) {
+    auto step4 = [&](f32x4 &q) {
+        const f32x4 gw = GradVec<GBF16>::widen(gv);
+        float G4[4] = {gw.x, gw.y, gw.z, gw.w};
+        float P4[4] = {q.x, q.y, q.z, q.w};
+        float A4[4] = {av.x, av.y, av.z, av.w};
+        float B4[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (ADAM)
+                adamw_one(G4[j], P4[j], A4[j], B4[j], s);
+            else
+                sgdm_one(G4[j], P4[j], A4[j], s);
+        }
+        q = f32x4{P4[0], P4[1], P4[2], P4[3]};
+        av = f32x4{A4[0], A4[1], A4[2], A4[3]};
+        bv = f32x4{B4[0], B4[1], B4[2], B4[3]};
+    };
+    if constexpr (UTS) step4(x);
+    f32x4 loc = x;
+    if constexpr (W16) loc = bf16_widen4(bf16_rne4(x));
+    f32x4 r[NREP];
+#pragma unroll
+    for (int k = 0; k < NREP; ++k) {
+        const f32x4 before = pv[k < NREP - 1 ? k : NREP - 2], after = pv[k > 0 ? k - 1 : 0];
+        r[k] = k == lr ? loc : (k < lr ? before : after);
+    }
+    f32x4 acc = r[0];
+#pragma unroll
+    for (int k = 1; k < NREP; ++k) acc = acc + r[k];
+    f32x4 m = acc * inv_n;
+    if constexpr (STATS) {
+#pragma unroll
+        for (int k = 0; k < NREP; ++k) {
+            const f32x4 d = m - r[k];
+            gsum += (double)d.x * (double)d.x;
+            gsum += (double)d.y * (double)d.y;
+            gsum += (double)d.z * (double)d.z;
+            gsum += (double)d.w * (double)d.w;
+        }
+        msum += (double)m.x * (double)m.x;
+        msum += (double)m.y * (double)m.y;
+        msum += (double)m.z * (double)m.z;
+        msum += (double)m.w * (double)m.w;
+    }
+    if constexpr (!UTS) step4(m);
+    x = m;
+}
 
 struct FusedArgs {
     const void *x[DDP_MAX_REPLICAS];  // peers' flat buffers (fp32 or bf16) in rank order; entry local_rank is unused
@@ -702,8 +882,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
         };
         if constexpr (NREP > 1) {
             // The local contribution may be computed (updated and / or rounded) and a branch per replica would
-            // serialise the loads: load the N-1 peers unconditionally, all in flight before the first use, then put
-            // the local value at position lr with register selects (lr is wave-uniform).
+            // serialise the loads: load the N-1 peers unconditionally, all in flight before the first use.
             for (int v = tid; v < nv; v += kThreads) {
                 f32x4 pv[NREP - 1];
 #pragma unroll
@@ -713,26 +892,8 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
                 f32x4 av = ld<NT>(a4 + v);
                 f32x4 bv{};
                 if constexpr (ADAM) bv = ld<NT>(b4 + v);
-                if constexpr (UTS) step4(gv, pl, av, bv);
-                f32x4 loc = pl;
-                if constexpr (W16) loc = bf16_widen4(bf16_rne4(pl));
-                f32x4 x[NREP];
-#pragma unroll
-                for (int k = 0; k < NREP; ++k) {
-                    const f32x4 before = pv[k < NREP - 1 ? k : NREP - 2], after = pv[k > 0 ? k - 1 : 0];
-                    x[k] = k == lr ? loc : (k < lr ? before : after);
-                }
-                f32x4 acc = x[0];
-#pragma unroll
-                for (int k = 1; k < NREP; ++k) acc = acc + x[k];
-                f32x4 m = acc * inv_n;
-                if constexpr (STATS) {
-#pragma unroll
-                    for (int k = 0; k < NREP; ++k) stats4(m, x[k]);
-                    msq4(m);
-                }
-                if constexpr (!UTS) step4(gv, m, av, bv);
-                store4(v, m, av, bv);
+                fused_math4<ADAM, GBF16, NREP, STATS, W16, UTS>(pv, gv, pl, av, bv, lr, inv_n, s, gsum, msum);
+                store4(v, pl, av, bv);
             }
         } else {
             for (int v = tid; v < nv; v += kThreads) {
@@ -764,6 +925,76 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
             const int64_t pi = (int64_t)a.tensor_chunk_base[ch.tensor] + ch.begin / a.chunk_elems;
             a.partials[2 * pi] = gt;
             a.partials[2 * pi + 1] = mt;
+        }
+    }
+}
+
+struct FusedDenseArgs {
+    DenseArgs d;                       // the scheduled layer's local streams; d.n is a multiple of 4
+    const void *x[DDP_MAX_REPLICAS];   // peers' whole flat buffers in rank order; entry local_rank is unused
+    int64_t fo0;                       // flat index of the layer's first element (a multiple of 4)
+    double *partials;                  // workgroup b writes its pair at partials[2 * (pbase + b)]
+    int64_t pbase;
+    float inv_n;
+    int local_rank;
+};
+
+// fused_kernel for one scheduled layer of a model registered as dense arenas: table-free addressing, buffer accesses
+// for all streams, the arithmetic of fused_math4.  Launched once per scheduled layer; the layers in between take
+// update_dense_kernel.
+template <bool ADAM, bool GBF16, bool MODEL, int NREP, bool STATS, bool W16, bool UTS>
+__global__ __launch_bounds__(kThreads) void fused_dense_kernel(const FusedDenseArgs a) {
+    typedef GradVec<GBF16> G;
+    typedef typename G::elem gelem;
+    typedef typename G::vec gvec;
+    static_assert(NREP > 1, "compile-time replica count");
+    constexpr int AUX = 2;                  // nt
+    constexpr int XB = W16 ? 8 : 16;        // bytes of one peer's group of four
+    __shared__ double lds[2][kThreads / kWave];
+    const int64_t b = (int64_t)blockIdx.x * a.d.chunk;
+    const int64_t left = a.d.n - b;
+    const int count = left < (int64_t)a.d.chunk ? (int)left : a.d.chunk;
+    const int nv = count >> 2;
+    const int tid = threadIdx.x;
+    const int lr = a.local_rank;
+    float *p = a.d.p + b;
+    float *s0 = a.d.s0 + b;
+    float *s1 = ADAM ? a.d.s1 + b : s0;
+    const gelem *g = reinterpret_cast<const gelem *>(a.d.g) + b;
+    unsigned short *mdl = MODEL ? a.d.mdl + b : reinterpret_cast<unsigned short *>(p);
+    const __amdgpu_buffer_rsrc_t rp = make_rsrc(p, nv * 16), ra = make_rsrc(s0, nv * 16), rb = make_rsrc(s1, nv * 16),
+                                 rg = make_rsrc(g, nv * (int)sizeof(gvec)), rm = make_rsrc(mdl, nv * 8);
+    __amdgpu_buffer_rsrc_t rx[NREP - 1];
+#pragma unroll
+    for (int j = 0; j < NREP - 1; ++j)
+        rx[j] = make_rsrc(reinterpret_cast<const char *>(a.x[j + (j >= lr ? 1 : 0)]) + (a.fo0 + b) * (XB / 4), nv * XB);
+    double gsum = 0.0, msum = 0.0;
+    for (int v = tid; v < nv; v += kThreads) {
+        f32x4 pv[NREP - 1];
+#pragma unroll
+        for (int j = 0; j < NREP - 1; ++j) {
+            if constexpr (W16)
+                pv[j] = bf16_widen4(bld<AUX, u16x4>(rx[j], v * XB));
+            else
+                pv[j] = bld<AUX, f32x4>(rx[j], v * XB);
+        }
+        f32x4 x = bld<AUX, f32x4>(rp, v * 16);
+        const gvec gv = bld<AUX, gvec>(rg, v * (int)sizeof(gvec));
+        f32x4 av = bld<AUX, f32x4>(ra, v * 16);
+        f32x4 bv{};
+        if constexpr (ADAM) bv = bld<AUX, f32x4>(rb, v * 16);
+        fused_math4<ADAM, GBF16, NREP, STATS, W16, UTS>(pv, gv, x, av, bv, lr, a.inv_n, a.d.s, gsum, msum);
+        bst<AUX>(rp, v * 16, x);
+        bst<AUX>(ra, v * 16, av);
+        if constexpr (ADAM) bst<AUX>(rb, v * 16, bv);
+        if constexpr (MODEL) bst<AUX>(rm, v * 8, bf16_rne4(x));
+    }
+    if constexpr (STATS) {
+        const double gt = block_sum(gsum, lds[0]);
+        const double mt = block_sum(msum, lds[1]);
+        if (tid == 0) {
+            a.partials[2 * (a.pbase + blockIdx.x)] = gt;
+            a.partials[2 * (a.pbase + blockIdx.x) + 1] = mt;
         }
     }
 }
@@ -871,6 +1102,91 @@ int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *t
     DDP_UPD(true, true, false)
     DDP_UPD(true, true, true)
 #undef DDP_UPD
+    return (int)hipErrorInvalidValue;
+}
+
+int launch_update_dense(int kind, int grad_dtype, bool with_model, const DenseLaunch &d, const UpdateScalars &s, bool nontemporal,
+                        int lds_pad, void *stream) {
+    if (d.n <= 0) return 0;
+    DenseArgs a{};
+    a.g = d.g;
+    a.p = d.p;
+    a.s0 = d.s0;
+    a.s1 = d.s1;
+    a.mdl = d.mdl;
+    a.n = d.n;
+    a.chunk = d.chunk;
+    a.s = s;
+    const int64_t grid = (d.n + d.chunk - 1) / d.chunk;
+    const bool adam = kind == DDP_OPT_ADAMW, gb = grad_dtype == DDP_BF16;
+#define DDP_UPD(A, G, M)                                                                                \
+    if (adam == A && gb == G && with_model == M)                                                        \
+        return nontemporal ? launch(update_dense_kernel<A, G, M, 2>, grid, stream, lds_pad, a)          \
+                           : launch(update_dense_kernel<A, G, M, 0>, grid, stream, lds_pad, a);
+    DDP_UPD(false, false, false)
+    DDP_UPD(false, false, true)
+    DDP_UPD(false, true, false)
+    DDP_UPD(false, true, true)
+    DDP_UPD(true, false, false)
+    DDP_UPD(true, false, true)
+    DDP_UPD(true, true, false)
+    DDP_UPD(true, true, true)
+#undef DDP_UPD
+    return (int)hipErrorInvalidValue;
+}
+
+template <bool A, bool G, bool M, int NR>
+static int launch_fused_dense_n(const FusedDenseLaunch &f, const FusedDenseArgs &fa, int64_t grid, void *stream) {
+    const bool st = f.partials != nullptr;
+#define DDP_FUSED(W, U)                                                                             \
+    return st ? launch(fused_dense_kernel<A, G, M, NR, true, W, U>, grid, stream, f.lds_pad, fa)    \
+              : launch(fused_dense_kernel<A, G, M, NR, false, W, U>, grid, stream, f.lds_pad, fa);
+    if (f.wire16) {
+        if (f.update_first) { DDP_FUSED(true, true) }
+        DDP_FUSED(true, false)
+    }
+    if (f.update_first) { DDP_FUSED(false, true) }
+    DDP_FUSED(false, false)
+#undef DDP_FUSED
+}
+
+bool fused_dense_supports(int n_replicas) { return n_replicas == 4 || n_replicas == 8 || n_replicas == 16; }
+
+int launch_fused_dense(const FusedDenseLaunch &f, void *stream) {
+    if (f.d.n <= 0) return 0;
+    FusedDenseArgs fa{};
+    fa.d.g = f.d.g;
+    fa.d.p = f.d.p;
+    fa.d.s0 = f.d.s0;
+    fa.d.s1 = f.d.s1;
+    fa.d.mdl = f.d.mdl;
+    fa.d.n = f.d.n;
+    fa.d.chunk = f.d.chunk;
+    fa.d.s = f.s;
+    for (int k = 0; k < f.n_replicas; ++k) fa.x[k] = f.x[k];
+    fa.fo0 = f.fo0;
+    fa.partials = f.partials;
+    fa.pbase = f.pbase;
+    fa.inv_n = f.inv_n;
+    fa.local_rank = f.local_rank;
+    const int64_t grid = (f.d.n + f.d.chunk - 1) / f.d.chunk;
+    const bool adam = f.kind == DDP_OPT_ADAMW, gb = f.grad_dtype == DDP_BF16, md = f.with_model;
+#define DDP_F(A, G, M)                                                                                  \
+    if (adam == A && gb == G && md == M) switch (f.n_replicas) {                                        \
+            case 4: return launch_fused_dense_n<A, G, M, 4>(f, fa, grid, stream);                       \
+            case 8: return launch_fused_dense_n<A, G, M, 8>(f, fa, grid, stream);                       \
+            case 16: return launch_fused_dense_n<A, G, M, 16>(f, fa, grid, stream);                     \
+            default: return (int)hipErrorInvalidValue;                                                  \
+        }
+    DDP_F(false, false, false)
+    DDP_F(false, false, true)
+    DDP_F(false, true, false)
+    DDP_F(false, true, true)
+    DDP_F(true, false, false)
+    DDP_F(true, false, true)
+    DDP_F(true, true, false)
+    DDP_F(true, true, true)
+#undef DDP_F
     return (int)hipErrorInvalidValue;
 }
 

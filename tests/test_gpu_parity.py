@@ -427,11 +427,16 @@ def test_bf16_wire_odd_shapes(oracle, arena_offset, fused):
 
 
 @pytest.mark.parametrize("options", [
+    {"dense_path": 0}, {"dense_path": 0, "update_chunk": 1024}, {"dense_path": 1, "update_chunk": 4096, "nontemporal": 0},
     {"dispatch_ways": 8}, {"dispatch_ways": 3, "update_chunk": 1024, "mean_chunk": 2048, "copy_chunk": 4096},
     {"update_lds": 0, "mean_lds": 0, "copy_lds": 0, "nontemporal": 0}, {"update_chunk": 1048576, "mean_chunk": 1048576, "copy_chunk": 1048576},
 ])
 def test_launch_options_do_not_change_results(oracle, options):
     t = run_trajectory(oracle, W.odd(n_replicas=8), options=options, arena_offset=2)
+    assert t.frac() == 1.0
+    t = run_trajectory(oracle, W.odd(n_replicas=8), options=options, arena_offset=0)      # dense arenas: the table-free update
+    assert t.frac() == 1.0
+    t = run_trajectory(oracle, W.small_llama(), options=options, iters=4)
     assert t.frac() == 1.0
     t = run_trajectory(oracle, W.small_llama(), options=options, fused=True, iters=4)
     assert t.frac() == 1.0
