@@ -120,13 +120,13 @@ int ddp_destroy(ddp_ctx *ctx);
 /* Tuning knobs.  The first two groups shape the tables built by ddp_register_model / ddp_set_schedule and must be
  * set before them (DDP_ESTATE otherwise); the others take effect at the next launch.
  *   "update_chunk", "mean_chunk", "copy_chunk"  elements per workgroup (multiple of 1024, 1024..1048576;
- *                                               defaults 2048 / 1024 / 2048)
+ *                                               defaults 2048 / 2048 / 2048)
  *   "dispatch_ways"                             1..4096 (default 1): launch order of the workgroups; w > 1 cuts every
  *                                               chunk table into w contiguous segments and visits them round-robin
  *   "update_lds", "mean_lds", "copy_lds"        0..65536 bytes of dynamic LDS requested per workgroup without being
  *                                               used: caps the workgroups resident per CU (160 KiB of LDS each), which
- *                                               keeps the window of DRAM rows in flight narrow (defaults 65536 / 53248 /
- *                                               24576 = 2 / 3 / 6 workgroups per CU)
+ *                                               keeps the window of DRAM rows in flight narrow (defaults 65536 / 65536 /
+ *                                               24576 = 2 / 2 / 6 workgroups per CU)
  *   "nontemporal"                               0/1 (default 1): streaming cache hints on loads and stores
  *   "dense_path"                                0/1 (default 1): when the registered tensors lie back to back in every
  *                                               stream (one arena per stream, starts 16-byte aligned, bf16 streams

@@ -163,10 +163,10 @@ struct ddp_ctx {
     int device = 0;
     mutable std::string err;
     // options
-    int64_t update_chunk = 2048, mean_chunk = 1024, copy_chunk = 2048;
+    int64_t update_chunk = 2048, mean_chunk = 2048, copy_chunk = 2048;
     bool nontemporal = true;
     int dispatch_ways = 1;
-    int update_lds = 65536, mean_lds = 53248, copy_lds = 24576;  // dynamic-LDS pad per workgroup: caps residency per CU
+    int update_lds = 65536, mean_lds = 65536, copy_lds = 24576;  // dynamic-LDS pad per workgroup: caps residency per CU
     // model
     bool registered = false;
     int L = 0, T = 0;

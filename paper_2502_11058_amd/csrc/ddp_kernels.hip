@@ -92,6 +92,34 @@ __device__ __forceinline__ f32x4 wire4(const void *base, int64_t v) {
         return ld<NT>(reinterpret_cast<const f32x4 *>(base) + v);
 }
 
+// Buffer (MUBUF) accesses: a per-workgroup descriptor (base in SGPRs, extent = the workgroup's part of the stream)
+// plus a 32-bit byte offset per lane.  Accesses past the extent read zero / are dropped by the hardware.
+// AUX: cache policy bits of the instruction (2 = nt, the streaming hint; 0 = default).
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, int bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);  // raw dword format
+}
+
+template <int AUX, class T>
+__device__ __forceinline__ T bld(__amdgpu_buffer_rsrc_t r, int byte_off) {
+    static_assert(sizeof(T) == 16 || sizeof(T) == 8, "128- or 64-bit access");
+    if constexpr (sizeof(T) == 16)
+        return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, AUX));
+    else
+        return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, AUX));
+}
+
+template <int AUX, class T>
+__device__ __forceinline__ void bst(__amdgpu_buffer_rsrc_t r, int byte_off, T v) {
+    static_assert(sizeof(T) == 16 || sizeof(T) == 8, "128- or 64-bit access");
+    if constexpr (sizeof(T) == 16)
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, byte_off, 0, AUX);
+    else
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), r, byte_off, 0, AUX);
+}
+
 __device__ __forceinline__ int head_to_16B(const void *p, int n) {  // fp32 elements until p is 16-byte aligned
     int h = (int)((4u - (unsigned)((reinterpret_cast<uintptr_t>(p) >> 2) & 3u)) & 3u);
     return h < n ? h : n;
@@ -309,14 +337,16 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
     };
 
     if constexpr (NREP > 0) {
-        constexpr int B = NREP <= 4 ? 4 : (NREP <= 8 ? 2 : 1);  // vectors per thread in flight: B * NREP loads
+        constexpr int B = NREP <= 8 ? 2 : 1;  // vectors per thread in flight: B * NREP loads (a 2048-element chunk is 2 vectors per thread)
+        auto rep4 = [&](int k, int idx) -> f32x4 { return wire4<W16, NT>(a.x[k], vbase + idx); };
+        auto put4 = [&](int idx, f32x4 m) { st<NT>(o4 + idx, m); };
         int v = tid;
         for (; v + (B - 1) * kThreads < nv; v += B * kThreads) {
             f32x4 x[B][NREP];
 #pragma unroll
             for (int b = 0; b < B; ++b)
 #pragma unroll
-                for (int k = 0; k < NREP; ++k) x[b][k] = wire4<W16, NT>(a.x[k], vbase + v + b * kThreads);
+                for (int k = 0; k < NREP; ++k) x[b][k] = rep4(k, v + b * kThreads);
 #pragma unroll
             for (int b = 0; b < B; ++b) {
                 f32x4 acc = x[b][0];
@@ -328,13 +358,13 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
                     for (int k = 0; k < NREP; ++k) stats4(m, x[b][k]);
                     msq4(m);
                 }
-                st<NT>(o4 + v + b * kThreads, m);
+                put4(v + b * kThreads, m);
             }
         }
         for (; v < nv; v += kThreads) {
             f32x4 x[NREP];
 #pragma unroll
-            for (int k = 0; k < NREP; ++k) x[k] = wire4<W16, NT>(a.x[k], vbase + v);
+            for (int k = 0; k < NREP; ++k) x[k] = rep4(k, v);
             f32x4 acc = x[0];
 #pragma unroll
             for (int k = 1; k < NREP; ++k) acc = acc + x[k];
@@ -344,7 +374,7 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
                 for (int k = 0; k < NREP; ++k) stats4(m, x[k]);
                 msq4(m);
             }
-            st<NT>(o4 + v, m);
+            put4(v, m);
         }
     } else {
         for (int v = tid; v < nv; v += kThreads) {
@@ -566,34 +596,6 @@ __global__ __launch_bounds__(kThreads) void update_kernel(const TensorDesc *__re
 // ---------------------------------------------------------------------------------------------------------------
 // local update over dense arenas
 // ---------------------------------------------------------------------------------------------------------------
-
-// Buffer (MUBUF) accesses: a per-workgroup descriptor (base in SGPRs, extent = the workgroup's part of the stream)
-// plus a 32-bit byte offset per lane.  Accesses past the extent read zero / are dropped by the hardware.
-// AUX: cache policy bits of the instruction (2 = nt, the streaming hint; 0 = default).
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, int bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);  // raw dword format
-}
-
-template <int AUX, class T>
-__device__ __forceinline__ T bld(__amdgpu_buffer_rsrc_t r, int byte_off) {
-    static_assert(sizeof(T) == 16 || sizeof(T) == 8, "128- or 64-bit access");
-    if constexpr (sizeof(T) == 16)
-        return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, AUX));
-    else
-        return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, AUX));
-}
-
-template <int AUX, class T>
-__device__ __forceinline__ void bst(__amdgpu_buffer_rsrc_t r, int byte_off, T v) {
-    static_assert(sizeof(T) == 16 || sizeof(T) == 8, "128- or 64-bit access");
-    if constexpr (sizeof(T) == 16)
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, byte_off, 0, AUX);
-    else
-        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), r, byte_off, 0, AUX);
-}
 
 struct DenseArgs {
     const void *g;  // the five streams at the first element of the range, each aligned for 128-bit (bf16: 64-bit) access
