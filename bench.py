@@ -106,6 +106,9 @@ def main() -> int:
                          "(bf16 matrix products standing in for each layer's BP); extra \"overlap\" object, never in value")
     ap.add_argument("--overlap-mm", type=int, default=4096, metavar="D",
                     help="edge of the square bf16 products of --overlap (4096: one product fills the 256 CUs)")
+    ap.add_argument("--front-pad-gib", type=int, default=None, metavar="G",
+                    help="leave G GiB unused at the start of the worker's slab (default: let the harness search a few values "
+                         "and keep the physical placement that streams fastest)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 4 plain elementwise copies of 1 GiB (torch.add(src, 0, out=dst)) before the timed region, "
                          "as the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
@@ -141,7 +144,11 @@ def main() -> int:
             torch.cuda.empty_cache()
         print(json.dumps({"placement_study_update_GBps": res, "workload": w.name}))
         return 0
-    rep = DeviceReplica(w, 0, options=options, policy=args.policy, wire16=args.wire16)
+    if args.front_pad_gib is None:
+        rep = DeviceReplica(w, 0, options=options, policy=args.policy, wire16=args.wire16,
+                            placement_probe="search" if w.n_params >= 1_000_000_000 else None)
+    else:
+        rep = DeviceReplica(w, 0, options=options, policy=args.policy, wire16=args.wire16, front_pad=args.front_pad_gib << 30)
     rep.init_params()
     rep.fill_grads(0)
     # peers: slot 0's packed local values + seeded drift; later slots reuse the staged bytes (same distribution)
@@ -302,7 +309,8 @@ def main() -> int:
         "config": {"workload": f"{w.name}: P={w.n_params}, N={w.n_replicas}, H={w.period}, {w.param_dtype} params, "
                                f"{w.optimizer}, schedule {args.policy or w.policy}, slot sizes {rep.slot_numel}",
                    "alg_bytes_per_step_avg": total_bytes / args.steps, "layer_stats": with_stats, "options": options,
-                   "placement_probe_GBps": [round(x, 1) for x in rep.placement["probe_GBps"]]},
+                   "placement_probe_GBps": [round(x, 1) for x in rep.placement["probe_GBps"]],
+                   "placement_front_pad_GiB": rep.placement.get("front_pad_GiB"), "placement_kept_GiB": rep.placement.get("kept_GiB", 0)},
         "kernels": kernels, "roofline": roofline, "fused": fused,
     }
     if wire16 is not None:
