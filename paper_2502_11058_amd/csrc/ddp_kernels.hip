@@ -337,7 +337,7 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
     };
 
     if constexpr (NREP > 0) {
-        constexpr int B = NREP <= 8 ? 2 : 1;  // vectors per thread in flight: B * NREP loads (a 2048-element chunk is 2 vectors per thread)
+        constexpr int B = 2;  // vectors per thread in flight: 2 * NREP loads (a 2048-element chunk is 2 vectors per thread)
         auto rep4 = [&](int k, int idx) -> f32x4 { return wire4<W16, NT>(a.x[k], vbase + idx); };
         auto put4 = [&](int idx, f32x4 m) { st<NT>(o4 + idx, m); };
         int v = tid;
