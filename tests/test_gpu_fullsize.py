@@ -25,6 +25,12 @@ def test_tinyllama_full_trajectory(oracle):
     assert t.frac() == 1.0
 
 
+@pytest.mark.timeout(900)
+def test_tinyllama_sampled_16_iterations(oracle):
+    # four periods with a million carried samples: the update's tolerance is stated after 16 iterations
+    assert run_sampled(oracle, W.tinyllama_1b(), iters=16) == 1.0
+
+
 def _sample_positions(rep, n_random, seed):
     P = int(rep.offsets[-1] - rep.offsets[0])
     rng = np.random.default_rng(seed)
