@@ -21,7 +21,8 @@
  *   - A context is not thread-safe; calls that share a context or device buffers must be ordered by the caller
  *     (stream order is enough): the statistics go through one reduction scratch per context.  The only calls that
  *     may be in flight together on one context are the layer-range calls, for disjoint ranges.
- *   - ddp_fused_sync_update does a2 + a3 + a4 of the list above in one pass over the model (no local flat buffer);
+ *   - ddp_fused_sync_update does average, unpack and update of the list above in one pass over the model (no local
+ *     flat buffer);
  *     the *_wire16 entry points exchange bf16 instead of fp32; the *_layers entry points act on a range of layers.
  *   - Layers are numbered 0..L-1 from the input side (the paper's layer 1) to the output side (layer L);
  *     the backward pass visits L-1, L-2, ..., 0.  Times are integer nanoseconds.
