@@ -47,7 +47,7 @@ def _sample_positions(rep, n_random, seed):
     return np.unique(np.concatenate(pos)) + int(rep.offsets[0])
 
 
-def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000, fused=False, wire16=False):
+def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000, fused=False, wire16=False, placement=None):
     from paper_2502_11058_amd.harness import DeviceReplica
     _need_gpu()
     oracle.set_threads(16)
@@ -55,7 +55,9 @@ def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000,
     torch.cuda.empty_cache()
     free, total_mem = torch.cuda.mem_get_info()
     progress(f"[{w.name}] HBM free {free / 1e9:.1f} GB of {total_mem / 1e9:.1f} GB")
-    rep = DeviceReplica(w, 0, wire16=wire16)
+    rep = DeviceReplica(w, 0, wire16=wire16, placement_probe=placement)
+    if placement:
+        progress(f"[{w.name}] placement {rep.placement}")
     rep.init_params()
     N, H = w.n_replicas, w.period
     dev = rep.dev
@@ -242,7 +244,8 @@ def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000,
 
 @pytest.mark.timeout(1500)
 def test_llama2_7b_sampled_trajectory(oracle):
-    assert run_sampled(oracle, W.llama2_7b(), iters=8) == 1.0
+    # the slab placed the way bench.py places it (placement search, front pad), default launch options
+    assert run_sampled(oracle, W.llama2_7b(), iters=8, placement="search") == 1.0
 
 
 @pytest.mark.timeout(1500)
