@@ -88,6 +88,19 @@ def cpu_baseline(rep, w, seconds_budget: float = 20.0):
             "params_per_s": S / sec}
 
 
+def gpu_clocks():
+    """Clock / performance state of GPU 0 as rocm-smi reports it after the run (best effort; None if unavailable)."""
+    import subprocess
+    try:
+        r = subprocess.run(["rocm-smi", "-d", "0", "--showclocks", "--showperflevel", "--json"], capture_output=True, text=True, timeout=20)
+        d = json.loads(r.stdout)
+        card = d[sorted(d)[0]]
+        keep = {k: v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "performance level"))}
+        return keep or None
+    except Exception:
+        return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -206,6 +219,7 @@ def main() -> int:
         evs.append((slot, e))
     torch.cuda.synchronize()
     kern = {n: {"ms": 0.0, "bytes": 0.0, "launches": 0} for n in names}
+    step_ms = sorted(e[0].elapsed_time(e[4]) for _, e in evs)           # one step = first to last event of its four calls
     for slot, e in evs:
         ab = algorithmic_bytes(w, rep.slot_numel[slot])
         for i, n in enumerate(names):
@@ -305,6 +319,7 @@ def main() -> int:
         "value": gbs, "unit": "GB/s", "pct_of_peak": 100.0 * gbs / HBM_PEAK_GBS,
         "params_per_s": w.n_params * args.steps / wall,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * wall / args.steps,
+        "step_ms_event_timed": {"median": step_ms[len(step_ms) // 2], "min": step_ms[0], "max": step_ms[-1]},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: P={w.n_params}, N={w.n_replicas}, H={w.period}, {w.param_dtype} params, "
                                f"{w.optimizer}, schedule {args.policy or w.policy}, slot sizes {rep.slot_numel}",
@@ -313,6 +328,7 @@ def main() -> int:
                    "placement_front_pad_GiB": rep.placement.get("front_pad_GiB"), "placement_kept_GiB": rep.placement.get("kept_GiB", 0)},
         "kernels": kernels, "roofline": roofline, "fused": fused,
     }
+    out["config"]["clocks"] = gpu_clocks()
     if wire16 is not None:
         out["wire16"] = wire16
     if overlap is not None:
