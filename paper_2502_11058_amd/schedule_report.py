@@ -1,6 +1,8 @@
 """Schedule quality on synthetic profiles, after the paper's Fig. 15: communication time that is not hidden by
 the backward pass, for the equal-number partition, Algorithm 2 and the exact optimum of Eq. (8), as the number
-of layers grows (H = 5) and as the bandwidth changes.  CPU only; uses the library's scheduler entry points.
+of layers grows (H = 5) and as the bandwidth changes; and, after its Fig. 16, the size of Algorithm 2's solution set
+and the search times against the number of cuts a brute-force search visits.  CPU only; uses the library's scheduler
+entry points.
 
     python -m paper_2502_11058_amd.schedule_report
 """
@@ -54,6 +56,29 @@ def bandwidth_sweep(name: str = "gpt2_small"):
     return rows
 
 
+def complexity_sweep(trials: int = 20, seed: int = 1):
+    """Per (L, H): cuts a brute force visits, C(L+H-1, H-1); the bound 2^min(L-1, H-1) on Algorithm 2's solution set;
+    the largest solution set seen over random profiles; median search time of Algorithm 2 and of the exact DP."""
+    import math
+    import time
+    rng = np.random.default_rng(seed)
+    rows = []
+    for L, H in ((8, 4), (16, 4), (32, 4), (32, 8), (64, 8), (128, 8), (128, 16), (256, 16)):
+        sizes, t_alg2, t_opt = [], [], []
+        for _ in range(trials):
+            nbytes = rng.integers(1 << 18, 1 << 24, L).astype(np.float64)
+            bp = np.rint(2.0 * nbytes * rng.uniform(0.8, 1.2, L)).astype(np.int64)
+            comm = np.rint(rng.uniform(2.0, 10.0) * nbytes).astype(np.int64)
+            sizes.append(B.ddp_schedule_alg2_solutions(bp, comm, H))
+            for pol, acc in (("alg2", t_alg2), ("opt", t_opt)):
+                t0 = time.perf_counter()
+                B.ddp_schedule(pol, L, H, bp // 2, bp, comm)
+                acc.append(time.perf_counter() - t0)
+        rows.append((L, H, math.comb(L + H - 1, H - 1), 2 ** min(L - 1, H - 1), max(sizes), 1e6 * float(np.median(t_alg2)),
+                     1e6 * float(np.median(t_opt))))
+    return rows
+
+
 def main() -> None:
     print("Excess of Eq. (8) over H backward passes (mean over 200 random profiles, H = 5), relative to H*t_BP")
     print(f"{'L':>3s} {'ENP':>8s} {'ALG2':>8s} {'OPT':>8s}  ALG2 == OPT")
@@ -63,6 +88,10 @@ def main() -> None:
     print(f"{'Gbps':>6s} {'FULL':>9s} {'ENP':>9s} {'ALG2':>9s} {'OPT':>9s}")
     for g, f, e, a, o in bandwidth_sweep():
         print(f"{g:6.2f} {f:9.1f} {e:9.1f} {a:9.1f} {o:9.1f}")
+    print("\nSearch effort: brute-force cuts, bound and largest observed size of Algorithm 2's solution set, search times")
+    print(f"{'L':>4s} {'H':>3s} {'brute-force cuts':>18s} {'2^min(L-1,H-1)':>15s} {'max |Omega|':>12s} {'ALG2 us':>9s} {'OPT us':>9s}")
+    for L, H, cuts, bound, size, ta, to in complexity_sweep():
+        print(f"{L:4d} {H:3d} {cuts:18.3e} {bound:15d} {size:12d} {ta:9.1f} {to:9.1f}")
 
 
 if __name__ == "__main__":

@@ -16,3 +16,12 @@ def test_period_time_falls_with_bandwidth_and_partial_sync_beats_full_sync():
         assert all(rows[i][col] >= rows[i + 1][col] for i in range(len(rows) - 1))
     for g, full, enp, alg2, opt in rows:
         assert opt <= alg2 <= enp <= full
+
+
+def test_solution_set_stays_within_its_bound_and_far_below_brute_force():
+    # Sec. 3.3: the pruned search visits exponentially fewer candidates than all cuts
+    for L, H, cuts, bound, size, t_alg2, t_opt in R.complexity_sweep(trials=5):
+        assert 1 <= size <= bound
+        assert cuts >= size
+    big = [r for r in R.complexity_sweep(trials=3) if r[0] >= 64]
+    assert all(r[2] > 1e6 * r[4] for r in big)
