@@ -208,8 +208,9 @@ int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream);
 /* Both cases of Eq. (5) in one pass over the model (the "sync into update" fusion): for the tensors of the slot's
  * layers the average over the N replicas is formed from the local tensor and the peers' flat buffers (read at the
  * tensor's flat offset of this slot) and the optimizer step is applied to it; all other tensors get the optimizer
- * step only.  Bit-identical to ddp_pack -> ddp_partial_average -> ddp_unpack -> ddp_local_update with the same
- * arguments, but the local flat buffer is never written or read: HBM traffic is 4(N-1) bytes per scheduled element
+ * step only.  Parameters, optimizer state and model copy are bit-identical to ddp_pack -> ddp_partial_average ->
+ * ddp_unpack -> ddp_local_update with the same arguments (the statistics agree to fp64 rounding: their partial sums are
+ * grouped differently), but the local flat buffer is never written or read: HBM traffic is 4(N-1) bytes per scheduled element
  * plus the update's bytes per parameter.  peers, N, local_rank, layer_stats as in ddp_partial_average; opt as in
  * ddp_local_update.  No flat_local / flat_out: the result lives in the model tensors only. */
 int ddp_fused_sync_update(ddp_ctx *ctx, int slot, const float *const *peers, int N, int local_rank, double *layer_stats,
