@@ -120,6 +120,21 @@ static bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintp
 
 using namespace ddp;
 
+// No C++ exception crosses the C boundary: the per-iteration entry points build messages and small host vectors, so a
+// failed host allocation is turned into DDP_ENOMEM here (the message itself may then be empty).
+template <class F>
+static int guarded(const ddp_ctx *ctx, F &&body) noexcept {
+    try {
+        return body();
+    } catch (...) {
+        try {
+            return fail(ctx, DDP_ENOMEM, "host allocation failed");
+        } catch (...) {
+            return DDP_ENOMEM;
+        }
+    }
+}
+
 extern "C" const char *ddp_last_error(const ddp_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
 
 extern "C" int ddp_create(ddp_ctx **out, int device) {
@@ -146,37 +161,39 @@ extern "C" int ddp_destroy(ddp_ctx *ctx) {
 }
 
 extern "C" int ddp_set_option(ddp_ctx *ctx, const char *name, int64_t value) {
-    if (!ctx || !name) return fail(ctx, DDP_EINVAL, "ddp_set_option: NULL argument");
-    std::string k(name);
-    auto chunk_ok = [&](int64_t v) { return v >= 1024 && v <= 1048576 && v % 1024 == 0; };
-    if (k == "update_chunk" || k == "mean_chunk" || k == "copy_chunk") {
-        if (!chunk_ok(value)) return fail(ctx, DDP_EINVAL, "ddp_set_option: chunk must be a multiple of 1024 in [1024, 1048576]");
-        if (ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_set_option: chunk sizes must be set before ddp_register_model");
-        (k == "update_chunk" ? ctx->update_chunk : k == "mean_chunk" ? ctx->mean_chunk : ctx->copy_chunk) = value;
-        return DDP_OK;
-    }
-    if (k == "dispatch_ways") {
-        if (value < 1 || value > 4096) return fail(ctx, DDP_EINVAL, "ddp_set_option: dispatch_ways must be in [1, 4096]");
-        if (ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_set_option: dispatch_ways must be set before ddp_register_model");
-        ctx->dispatch_ways = (int)value;
-        return DDP_OK;
-    }
-    if (k == "update_lds" || k == "mean_lds" || k == "copy_lds") {
-        if (value < 0 || value > 65536) return fail(ctx, DDP_EINVAL, "ddp_set_option: LDS pad must be in [0, 65536] bytes");
-        (k == "update_lds" ? ctx->update_lds : k == "mean_lds" ? ctx->mean_lds : ctx->copy_lds) = (int)value;
-        return DDP_OK;
-    }
-    if (k == "dense_path") {
-        if (value != 0 && value != 1) return fail(ctx, DDP_EINVAL, "ddp_set_option: dense_path is 0 or 1");
-        ctx->dense_path = value != 0;
-        return DDP_OK;
-    }
-    if (k == "nontemporal") {
-        if (value != 0 && value != 1) return fail(ctx, DDP_EINVAL, "ddp_set_option: nontemporal is 0 or 1");
-        ctx->nontemporal = value != 0;
-        return DDP_OK;
-    }
-    return fail(ctx, DDP_EINVAL, "ddp_set_option: unknown option " + k);
+    return guarded(ctx, [&]() -> int {
+        if (!ctx || !name) return fail(ctx, DDP_EINVAL, "ddp_set_option: NULL argument");
+        std::string k(name);
+        auto chunk_ok = [&](int64_t v) { return v >= 1024 && v <= 1048576 && v % 1024 == 0; };
+        if (k == "update_chunk" || k == "mean_chunk" || k == "copy_chunk") {
+            if (!chunk_ok(value)) return fail(ctx, DDP_EINVAL, "ddp_set_option: chunk must be a multiple of 1024 in [1024, 1048576]");
+            if (ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_set_option: chunk sizes must be set before ddp_register_model");
+            (k == "update_chunk" ? ctx->update_chunk : k == "mean_chunk" ? ctx->mean_chunk : ctx->copy_chunk) = value;
+            return DDP_OK;
+        }
+        if (k == "dispatch_ways") {
+            if (value < 1 || value > 4096) return fail(ctx, DDP_EINVAL, "ddp_set_option: dispatch_ways must be in [1, 4096]");
+            if (ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_set_option: dispatch_ways must be set before ddp_register_model");
+            ctx->dispatch_ways = (int)value;
+            return DDP_OK;
+        }
+        if (k == "update_lds" || k == "mean_lds" || k == "copy_lds") {
+            if (value < 0 || value > 65536) return fail(ctx, DDP_EINVAL, "ddp_set_option: LDS pad must be in [0, 65536] bytes");
+            (k == "update_lds" ? ctx->update_lds : k == "mean_lds" ? ctx->mean_lds : ctx->copy_lds) = (int)value;
+            return DDP_OK;
+        }
+        if (k == "dense_path") {
+            if (value != 0 && value != 1) return fail(ctx, DDP_EINVAL, "ddp_set_option: dense_path is 0 or 1");
+            ctx->dense_path = value != 0;
+            return DDP_OK;
+        }
+        if (k == "nontemporal") {
+            if (value != 0 && value != 1) return fail(ctx, DDP_EINVAL, "ddp_set_option: nontemporal is 0 or 1");
+            ctx->nontemporal = value != 0;
+            return DDP_OK;
+        }
+        return fail(ctx, DDP_EINVAL, "ddp_set_option: unknown option " + k);
+    });
 }
 
 extern "C" int ddp_register_model(ddp_ctx *ctx, int L, int T, const int32_t *layer_of, const int64_t *numel, int param_dtype,
@@ -445,26 +462,30 @@ static int check_flat(const ddp_ctx *ctx, const void *p, const char *who, const 
 }
 
 extern "C" int ddp_pack(ddp_ctx *ctx, int slot, float *flat_local, void *stream) {
-    int rc;
-    const SlotTables *s = slot_of(ctx, slot, "ddp_pack", &rc);
-    if (!s) return rc;
-    if ((rc = check_device(ctx, "ddp_pack")) != DDP_OK) return rc;
-    if (s->numel == 0) return DDP_OK;
-    if ((rc = check_flat(ctx, flat_local, "ddp_pack", "flat_local")) != DDP_OK) return rc;
-    rc = launch_copy(false, ctx->d_tensors, s->d_copy, s->n_copy, flat_local, false, ctx->nontemporal, ctx->copy_lds, stream);
-    return after_launch(ctx, "ddp_pack", rc);
+    return guarded(ctx, [&]() -> int {
+        int rc;
+        const SlotTables *s = slot_of(ctx, slot, "ddp_pack", &rc);
+        if (!s) return rc;
+        if ((rc = check_device(ctx, "ddp_pack")) != DDP_OK) return rc;
+        if (s->numel == 0) return DDP_OK;
+        if ((rc = check_flat(ctx, flat_local, "ddp_pack", "flat_local")) != DDP_OK) return rc;
+        rc = launch_copy(false, ctx->d_tensors, s->d_copy, s->n_copy, flat_local, false, ctx->nontemporal, ctx->copy_lds, stream);
+        return after_launch(ctx, "ddp_pack", rc);
+    });
 }
 
 extern "C" int ddp_unpack(ddp_ctx *ctx, int slot, const float *flat, void *stream) {
-    int rc;
-    const SlotTables *s = slot_of(ctx, slot, "ddp_unpack", &rc);
-    if (!s) return rc;
-    if ((rc = check_device(ctx, "ddp_unpack")) != DDP_OK) return rc;
-    if (s->numel == 0) return DDP_OK;
-    if ((rc = check_flat(ctx, flat, "ddp_unpack", "flat")) != DDP_OK) return rc;
-    rc = launch_copy(true, ctx->d_tensors, s->d_copy, s->n_copy, const_cast<float *>(flat), ctx->param_dtype == DDP_BF16,
-                     ctx->nontemporal, ctx->copy_lds, stream);
-    return after_launch(ctx, "ddp_unpack", rc);
+    return guarded(ctx, [&]() -> int {
+        int rc;
+        const SlotTables *s = slot_of(ctx, slot, "ddp_unpack", &rc);
+        if (!s) return rc;
+        if ((rc = check_device(ctx, "ddp_unpack")) != DDP_OK) return rc;
+        if (s->numel == 0) return DDP_OK;
+        if ((rc = check_flat(ctx, flat, "ddp_unpack", "flat")) != DDP_OK) return rc;
+        rc = launch_copy(true, ctx->d_tensors, s->d_copy, s->n_copy, const_cast<float *>(flat), ctx->param_dtype == DDP_BF16,
+                         ctx->nontemporal, ctx->copy_lds, stream);
+        return after_launch(ctx, "ddp_unpack", rc);
+    });
 }
 
 // Shared body of the two averaging entry points; `who` names the caller in messages.  wire16: the replicas are
@@ -522,25 +543,31 @@ static int partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int 
 
 extern "C" int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_local, const float *const *peers, int N,
                                    int local_rank, float *flat_out, double *layer_stats, void *stream) {
-    return partial_average_impl(ctx, "ddp_partial_average", false, slot, flat_local, reinterpret_cast<const void *const *>(peers), N,
-                                local_rank, flat_out, layer_stats, stream);
+    return guarded(ctx, [&]() -> int {
+        return partial_average_impl(ctx, "ddp_partial_average", false, slot, flat_local, reinterpret_cast<const void *const *>(peers), N,
+                                    local_rank, flat_out, layer_stats, stream);
+    });
 }
 
 extern "C" int ddp_pack_wire16(ddp_ctx *ctx, int slot, uint16_t *flat_local16, void *stream) {
-    int rc;
-    const SlotTables *s = slot_of(ctx, slot, "ddp_pack_wire16", &rc);
-    if (!s) return rc;
-    if ((rc = check_device(ctx, "ddp_pack_wire16")) != DDP_OK) return rc;
-    if (s->numel == 0) return DDP_OK;
-    if ((rc = check_flat(ctx, flat_local16, "ddp_pack_wire16", "flat_local16")) != DDP_OK) return rc;
-    rc = launch_pack16(ctx->d_tensors, s->d_copy, s->n_copy, flat_local16, ctx->nontemporal, ctx->copy_lds, stream);
-    return after_launch(ctx, "ddp_pack_wire16", rc);
+    return guarded(ctx, [&]() -> int {
+        int rc;
+        const SlotTables *s = slot_of(ctx, slot, "ddp_pack_wire16", &rc);
+        if (!s) return rc;
+        if ((rc = check_device(ctx, "ddp_pack_wire16")) != DDP_OK) return rc;
+        if (s->numel == 0) return DDP_OK;
+        if ((rc = check_flat(ctx, flat_local16, "ddp_pack_wire16", "flat_local16")) != DDP_OK) return rc;
+        rc = launch_pack16(ctx->d_tensors, s->d_copy, s->n_copy, flat_local16, ctx->nontemporal, ctx->copy_lds, stream);
+        return after_launch(ctx, "ddp_pack_wire16", rc);
+    });
 }
 
 extern "C" int ddp_partial_average_wire16(ddp_ctx *ctx, int slot, const uint16_t *flat_local16, const uint16_t *const *peers16, int N,
                                           int local_rank, float *flat_out, double *layer_stats, void *stream) {
-    return partial_average_impl(ctx, "ddp_partial_average_wire16", true, slot, flat_local16,
-                                reinterpret_cast<const void *const *>(peers16), N, local_rank, flat_out, layer_stats, stream);
+    return guarded(ctx, [&]() -> int {
+        return partial_average_impl(ctx, "ddp_partial_average_wire16", true, slot, flat_local16,
+                                    reinterpret_cast<const void *const *>(peers16), N, local_rank, flat_out, layer_stats, stream);
+    });
 }
 
 static int make_scalars(ddp_ctx *ctx, const char *who, const ddp_opt *opt, UpdateScalars &s) {
@@ -623,11 +650,15 @@ static int local_update_impl(ddp_ctx *ctx, const char *who, bool whole, int firs
 }
 
 extern "C" int ddp_local_update(ddp_ctx *ctx, const ddp_opt *opt, void *stream) {
-    return local_update_impl(ctx, "ddp_local_update", true, 0, 0, opt, stream);
+    return guarded(ctx, [&]() -> int {
+        return local_update_impl(ctx, "ddp_local_update", true, 0, 0, opt, stream);
+    });
 }
 
 extern "C" int ddp_local_update_layers(ddp_ctx *ctx, int layer_first, int layer_count, const ddp_opt *opt, void *stream) {
-    return local_update_impl(ctx, "ddp_local_update_layers", false, layer_first, layer_count, opt, stream);
+    return guarded(ctx, [&]() -> int {
+        return local_update_impl(ctx, "ddp_local_update_layers", false, layer_first, layer_count, opt, stream);
+    });
 }
 
 // The fused step over layers [first, first + count) of a model registered as dense arenas: one table-free launch per
@@ -787,21 +818,27 @@ static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, bool update_fi
 
 extern "C" int ddp_fused_sync_update(ddp_ctx *ctx, int slot, const float *const *peers, int N, int local_rank, double *layer_stats,
                                      const ddp_opt *opt, void *stream) {
-    return fused_impl(ctx, "ddp_fused_sync_update", false, false, slot, true, 0, 0, reinterpret_cast<const void *const *>(peers), N, local_rank,
-                      layer_stats, opt, stream);
+    return guarded(ctx, [&]() -> int {
+        return fused_impl(ctx, "ddp_fused_sync_update", false, false, slot, true, 0, 0, reinterpret_cast<const void *const *>(peers), N, local_rank,
+                          layer_stats, opt, stream);
+    });
 }
 
 extern "C" int ddp_fused_sync_update_wire16(ddp_ctx *ctx, int slot, const uint16_t *const *peers16, int N, int local_rank,
                                             double *layer_stats, const ddp_opt *opt, void *stream) {
-    return fused_impl(ctx, "ddp_fused_sync_update_wire16", true, false, slot, true, 0, 0, reinterpret_cast<const void *const *>(peers16), N,
-                      local_rank, layer_stats, opt, stream);
+    return guarded(ctx, [&]() -> int {
+        return fused_impl(ctx, "ddp_fused_sync_update_wire16", true, false, slot, true, 0, 0, reinterpret_cast<const void *const *>(peers16), N,
+                          local_rank, layer_stats, opt, stream);
+    });
 }
 
 extern "C" int ddp_fused_sync_update_layers(ddp_ctx *ctx, int slot, int layer_first, int layer_count, const void *const *peers,
                                             int wire_dtype, int order, int N, int local_rank, double *layer_stats, const ddp_opt *opt,
                                             void *stream) {
-    if (wire_dtype != DDP_F32 && wire_dtype != DDP_BF16) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update_layers: bad wire_dtype");
-    if (order != DDP_SYNC_THEN_UPDATE && order != DDP_UPDATE_THEN_SYNC) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update_layers: bad order");
-    return fused_impl(ctx, "ddp_fused_sync_update_layers", wire_dtype == DDP_BF16, order == DDP_UPDATE_THEN_SYNC, slot, false, layer_first,
-                      layer_count, peers, N, local_rank, layer_stats, opt, stream);
+    return guarded(ctx, [&]() -> int {
+        if (wire_dtype != DDP_F32 && wire_dtype != DDP_BF16) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update_layers: bad wire_dtype");
+        if (order != DDP_SYNC_THEN_UPDATE && order != DDP_UPDATE_THEN_SYNC) return fail(ctx, DDP_EINVAL, "ddp_fused_sync_update_layers: bad order");
+        return fused_impl(ctx, "ddp_fused_sync_update_layers", wire_dtype == DDP_BF16, order == DDP_UPDATE_THEN_SYNC, slot, false, layer_first,
+                          layer_count, peers, N, local_rank, layer_stats, opt, stream);
+    });
 }
