@@ -66,8 +66,8 @@ class DeviceReplica:
             placement_probe = P >= 1_000_000_000
         if placement_probe == "search":
             # Where the slab lands physically depends on the size of the allocation and on the offset of the data
-            # inside it; the update kernel's rate varies by a few per cent with it (same kernel, same virtual layout).
-            # Try a few unused front pads, keep the fastest, allocate it again and check that it still is.
+            # inside it; the kernels' rates vary by a few per cent with it (same kernels, same virtual layout).
+            # Try a few unused front pads, time one pass of the four-call step over all slots on each, keep the fastest.
             GiB = 1 << 30
             body = self.slab.numel() - self.front_pad
             total = torch.cuda.get_device_properties(self.dev).total_memory
@@ -79,13 +79,13 @@ class DeviceReplica:
                     self._release()
                     self.front_pad = pad
                     self._build()
-                tried.append((self._probe(), pad))
+                tried.append((self._probe_step(), pad))
             best_rate, best_pad = max(tried)
             if self.front_pad != best_pad:
                 self._release()
                 self.front_pad = best_pad
                 self._build()
-                tried.append((self._probe(), best_pad))
+                tried.append((self._probe_step(), best_pad))
             self.placement = {"probe_GBps": [r for r, _ in tried], "front_pad_GiB": [p // GiB for _, p in tried], "kept_GiB": best_pad // GiB}
         elif placement_probe:
             # Successive allocations of a slab this large alternate between two physical placements whose DRAM
@@ -128,6 +128,23 @@ class DeviceReplica:
         torch.cuda.synchronize()
         ms = sorted(a.elapsed_time(b) for a, b in evs[1:])
         return per * P / (ms[len(ms) // 2] * 1e-3) / 1e9
+
+    def _probe_step(self) -> float:
+        """GB/s of the whole four-call step on the zeroed slab, one pass over the slots (zeros stay zeros)."""
+        stream = torch.cuda.current_stream()
+        P = self._regions_args[0]
+        per = (2 if self.grad_bf16 else 4) + (24 if self.adam else 16) + (2 if self.bf16 else 0)
+        N = len(self.peers) + 1
+        self.step(0)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        nbytes = 0.0
+        for r in range(len(self.sets)):
+            self.step(r)
+            nbytes += per * P + (8 + 4 * (N + 1) + (10 if self.bf16 else 8)) * self.slot_numel[r]
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
     def _build(self) -> None:
         P, arena_offset, smax, n_peers, max_layers, region_skew, sp, sl, _, _ = self._regions_args
