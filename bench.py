@@ -89,16 +89,28 @@ def cpu_baseline(rep, w, seconds_budget: float = 20.0):
 
 
 def gpu_clocks():
-    """Clock / performance state of GPU 0 as rocm-smi reports it after the run (best effort; None if unavailable)."""
-    import subprocess
-    try:
-        r = subprocess.run(["rocm-smi", "-d", "0", "--showclocks", "--showperflevel", "--json"], capture_output=True, text=True, timeout=20)
-        d = json.loads(r.stdout)
-        card = d[sorted(d)[0]]
-        keep = {k: v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "performance level"))}
-        return keep or None
-    except Exception:
-        return None
+    """Clock / performance state of the first AMD GPU from sysfs, read after the run (plain file reads: no child
+    process is started from a process that holds the GPU).  None if the files are not there."""
+    import glob
+    for dev in sorted(glob.glob("/sys/class/drm/card*/device")):
+        try:
+            if open(os.path.join(dev, "vendor")).read().strip() != "0x1002":
+                continue
+            out = {}
+            for key, name in (("sclk", "pp_dpm_sclk"), ("mclk", "pp_dpm_mclk"), ("fclk", "pp_dpm_fclk")):
+                path = os.path.join(dev, name)
+                if os.path.exists(path):
+                    cur = [ln.split(":", 1)[1].replace("*", "").strip() for ln in open(path).read().splitlines() if ln.strip().endswith("*")]
+                    if cur:
+                        out[key] = cur[0]
+            path = os.path.join(dev, "power_dpm_force_performance_level")
+            if os.path.exists(path):
+                out["performance_level"] = open(path).read().strip()
+            if out:
+                return out
+        except OSError:
+            continue
+    return None
 
 
 def main() -> int:
