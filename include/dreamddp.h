@@ -131,7 +131,8 @@ int ddp_destroy(ddp_ctx *ctx);
  *   "update_lds", "mean_lds", "copy_lds"        0..65536 bytes of dynamic LDS requested per workgroup without being
  *                                               used: caps the workgroups resident per CU (160 KiB of LDS each), which
  *                                               keeps the window of DRAM rows in flight narrow (defaults 65536 / 65536 /
- *                                               24576 = 2 / 2 / 6 workgroups per CU)
+ *                                               24576 = 2 / 2 / 6 workgroups per CU; the bf16-wire average uses half
+ *                                               of mean_lds)
  *   "nontemporal"                               0/1 (default 1): streaming cache hints on loads and stores
  *   "dense_path"                                0/1 (default 1): when the registered tensors lie back to back in every
  *                                               stream (one arena per stream, starts 16-byte aligned, bf16 streams

@@ -536,7 +536,8 @@ static int partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int 
     a.n_layers = (int)s->layers.size();
     a.stats = layer_stats;
     a.nontemporal = ctx->nontemporal;
-    a.lds_pad = ctx->mean_lds;
+    // bf16 replicas put half the bytes per workgroup in flight: half the pad, twice the workgroups per CU
+    a.lds_pad = wire16 ? ctx->mean_lds / 2 : ctx->mean_lds;
     rc = launch_mean(a, stream);
     return after_launch(ctx, who, rc);
 }
