@@ -72,13 +72,13 @@ class DeviceReplica:
             body = self.slab.numel() - self.front_pad
             total = torch.cuda.get_device_properties(self.dev).total_memory
             tried = []
+            tried.append((self._probe_step(), self.front_pad))      # the slab built above is the first candidate
             for pad in (0, 16 * GiB, 24 * GiB, 32 * GiB, 40 * GiB):
-                if body + pad + 6 * GiB > total:
+                if pad == tried[0][1] or body + pad + 6 * GiB > total:
                     continue
-                if tried or pad != self.front_pad:     # the slab built above serves as the first candidate
-                    self._release()
-                    self.front_pad = pad
-                    self._build()
+                self._release()
+                self.front_pad = pad
+                self._build()
                 tried.append((self._probe_step(), pad))
             best_rate, best_pad = max(tried)
             if self.front_pad != best_pad:
