@@ -47,7 +47,8 @@ def _sample_positions(rep, n_random, seed):
     return np.unique(np.concatenate(pos)) + int(rep.offsets[0])
 
 
-def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000, fused=False, wire16=False, placement=None):
+def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000, fused=False, wire16=False, placement=None,
+                layerwise=0):
     from paper_2502_11058_amd.harness import DeviceReplica
     _need_gpu()
     oracle.set_threads(16)
@@ -71,6 +72,7 @@ def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000,
     assert np.array_equal(_np(rep.a_model[gi]), model_s)
     inv_n = torch.tensor(1.0 / N, dtype=torch.float32, device=dev)
     n_exact = n_total = 0
+    side = torch.cuda.Stream() if layerwise else None
 
     for r in range(iters):
         slot, S, rank = r % H, rep.sets[r % H], r % N
@@ -123,7 +125,11 @@ def run_sampled(oracle, w, iters, n_random=1 << 20, stats_layer_cap=260_000_000,
             rep.stats.fill_(-1.0)
             if fused:
                 del base
-                if wire16:
+                if layerwise:
+                    # buckets of layers on a side stream, the way a backward pass would release them (gradients are
+                    # already in place here, so the "backward" of a layer is empty)
+                    rep.layerwise_step(r, side, backward=lambda l: None, bucket=layerwise, local_rank=rank, wire16=wire16)
+                elif wire16:
                     rep.ctx.ddp_fused_sync_update_wire16(slot, rep.peers16, N, rank, rep.stats, rep.opt_struct(r + 1))
                 else:
                     rep.ctx.ddp_fused_sync_update(slot, rep.peers, N, rank, rep.stats, rep.opt_struct(r + 1))
@@ -251,6 +257,12 @@ def test_llama2_7b_sampled_trajectory(oracle):
 @pytest.mark.timeout(1500)
 def test_llama2_7b_fused_sampled_trajectory(oracle):
     assert run_sampled(oracle, W.llama2_7b(), iters=8, fused=True) == 1.0
+
+
+@pytest.mark.timeout(1500)
+def test_llama2_7b_layerwise_fused_sampled_trajectory(oracle):
+    # the fused step as 12 launches of three layers each on a side stream (Sec. 3.2 granularity) instead of one call
+    assert run_sampled(oracle, W.llama2_7b(), iters=4, fused=True, layerwise=3) == 1.0
 
 
 @pytest.mark.timeout(1500)
