@@ -29,16 +29,9 @@ constexpr int kWave = 64;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
 
-#ifndef DDP_NT_LOADS
-#define DDP_NT_LOADS 1
-#endif
-#ifndef DDP_NT_STORES
-#define DDP_NT_STORES 1
-#endif
-
 template <bool NT, class T>
 __device__ __forceinline__ T ld(const T *p) {
-    if constexpr (NT && DDP_NT_LOADS)
+    if constexpr (NT)
         return __builtin_nontemporal_load(p);
     else
         return *p;
@@ -46,7 +39,7 @@ __device__ __forceinline__ T ld(const T *p) {
 
 template <bool NT, class T>
 __device__ __forceinline__ void st(T *p, T v) {
-    if constexpr (NT && DDP_NT_STORES)
+    if constexpr (NT)
         __builtin_nontemporal_store(v, p);
     else
         *p = v;
