@@ -33,6 +33,19 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert sorted(B.EXPORTS) == declared
 
 
+def test_missing_library_fails_loudly_no_fallback():
+    # the product path has no CPU fallback: without the built library every entry point raises
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("from paper_2502_11058_amd import binding as B\n"
+            "try:\n    B.ddp_schedule('enp', 4, 2, None, None, None)\nexcept FileNotFoundError as e:\n    print('missing:', e)\n")
+    env = dict(os.environ, DREAMDDP_LIB="/nonexistent/libdreamddp.so", PYTHONPATH=root)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env, timeout=300)
+    assert r.returncode == 0 and "missing: /nonexistent/libdreamddp.so is missing" in r.stdout, r.stdout + r.stderr
+
+
 def test_create_without_gpu_fails_cleanly():
     import torch
     if torch.cuda.is_available():
