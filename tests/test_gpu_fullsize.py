@@ -20,8 +20,9 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.timeout(1500)
 def test_tinyllama_full_trajectory(oracle):
-    # every element of every stage against the oracle, two full periods (H = 4); the CPU oracle is the slow side here
-    t = run_trajectory(oracle, W.tinyllama_1b(), iters=8, check_every=4)
+    # every element of every stage against the oracle, one full period (H = 4: every slot once); the CPU oracle is the
+    # slow side here, the 16-iteration horizon is covered by the sampled run below
+    t = run_trajectory(oracle, W.tinyllama_1b(), iters=4, check_every=4)
     assert t.frac() == 1.0
 
 
