@@ -1,10 +1,11 @@
 // gfx950 kernels of the partial-synchronisation + local-update step (Algorithm 1 / Eq. (5) of the paper).
 //
-// All four kernels are HBM streaming kernels (well under 1 flop per byte): no MFMA, no data reuse.  The design
+// All kernels are HBM streaming kernels (well under 1 flop per byte): no MFMA, no data reuse.  The design
 // rules are the same everywhere:
 //   - one workgroup (256 threads = 4 wavefronts of 64) per table entry ("chunk"), a run of elements inside one
 //     tensor or one layer, so the ragged boundaries of tensors and layers are handled by the table, not by
-//     per-element searches;
+//     per-element searches; where the registered tensors form dense arenas the update and the fused step need no
+//     table at all (the *_dense_kernel variants: addresses from the block index, buffer accesses);
 //   - inside a chunk: a scalar head of < 4 elements up to the next 16-byte boundary of the destination, a body
 //     of 128-bit accesses (lane i of a wavefront touches bytes [16i, 16i+16) of a 1 KiB line, fully coalesced),
 //     and a scalar tail of < 4 elements;
