@@ -327,6 +327,7 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
         int64_t max_mean_chunks = 0;
         for (int s = 0; s < H; ++s) {
             SlotTables &st = slots[(size_t)s];
+            st.layer_pos.assign((size_t)ctx->L, -1);
             std::vector<CopyChunk> cc;
             std::vector<MeanChunk> mc;
             std::vector<int32_t> lcp, fused_ranges;
@@ -339,6 +340,7 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
                 lcp.push_back((int32_t)mc.size());
                 fused_ranges.push_back(ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)l]]);
                 fused_ranges.push_back(ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)l + 1]]);
+                st.layer_pos[(size_t)l] = (int32_t)st.layers.size() - 1;
                 st.dense_ranges.push_back((int32_t)dense_wg_base[(size_t)l]);
                 st.dense_ranges.push_back((int32_t)dense_wg_base[(size_t)l + 1]);
                 const int64_t layer_start = off;
@@ -493,17 +495,16 @@ extern "C" int ddp_unpack(ddp_ctx *ctx, int slot, const float *flat, void *strea
 static int partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, const void *flat_local, const void *const *peers,
                                 int N, int local_rank, float *flat_out, double *layer_stats, void *stream) {
     int rc;
-    const std::string w(who);
     const SlotTables *s = slot_of(ctx, slot, who, &rc);
     if (!s) return rc;
     if ((rc = check_device(ctx, who)) != DDP_OK) return rc;
-    if (N < 1 || N > DDP_MAX_REPLICAS) return fail(ctx, DDP_EINVAL, w + ": N must be in [1, " + std::to_string((int)DDP_MAX_REPLICAS) + "]");
-    if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, w + ": local_rank out of range");
-    if (N > 1 && !peers) return fail(ctx, DDP_EINVAL, w + ": peers is NULL");
+    if (N < 1 || N > DDP_MAX_REPLICAS) return fail(ctx, DDP_EINVAL, std::string(who) + ": N must be in [1, " + std::to_string((int)DDP_MAX_REPLICAS) + "]");
+    if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, std::string(who) + ": local_rank out of range");
+    if (N > 1 && !peers) return fail(ctx, DDP_EINVAL, std::string(who) + ": peers is NULL");
     if (s->numel == 0) return DDP_OK;
     if ((rc = check_flat(ctx, flat_local, who, "flat_local")) != DDP_OK) return rc;
     if ((rc = check_flat(ctx, flat_out, who, "flat_out")) != DDP_OK) return rc;
-    if (layer_stats && !aligned(layer_stats, 8)) return fail(ctx, DDP_EALIGN, w + ": layer_stats must be 8-byte aligned");
+    if (layer_stats && !aligned(layer_stats, 8)) return fail(ctx, DDP_EALIGN, std::string(who) + ": layer_stats must be 8-byte aligned");
     const uintptr_t out_bytes = (uintptr_t)s->numel * 4, in_bytes = (uintptr_t)s->numel * (wire16 ? 2 : 4);
     auto overlaps_out = [&](const void *in) {
         uintptr_t x = (uintptr_t)in, y = (uintptr_t)flat_out;
@@ -511,7 +512,7 @@ static int partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int 
     };
     // fp32: exactly in place is fine (each element is read before it is written by the same thread)
     if (!(flat_out == flat_local && !wire16) && overlaps_out(flat_local))
-        return fail(ctx, DDP_EINVAL, w + (wire16 ? ": flat_out overlaps flat_local" : ": flat_out partially overlaps flat_local"));
+        return fail(ctx, DDP_EINVAL, std::string(who) + (wire16 ? ": flat_out overlaps flat_local" : ": flat_out partially overlaps flat_local"));
     MeanLaunch a{};
     int p = 0;
     for (int k = 0; k < N; ++k) {
@@ -521,7 +522,7 @@ static int partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int 
         }
         const void *q = peers[p++];
         if ((rc = check_flat(ctx, q, who, "a peer buffer")) != DDP_OK) return rc;
-        if (overlaps_out(q)) return fail(ctx, DDP_EINVAL, w + ": a peer buffer overlaps flat_out");
+        if (overlaps_out(q)) return fail(ctx, DDP_EINVAL, std::string(who) + ": a peer buffer overlaps flat_out");
         a.x[k] = q;
     }
     a.wire16 = wire16;
@@ -601,11 +602,10 @@ static int make_scalars(ddp_ctx *ctx, const char *who, const ddp_opt *opt, Updat
 // Chunk range [c0, c1) of the update table that covers layers [first, first + count); needs the table in
 // registration order.
 static int layer_chunk_range(ddp_ctx *ctx, const char *who, int first, int count, int64_t *c0, int64_t *c1) {
-    const std::string w(who);
     if (first < 0 || count < 0 || first > ctx->L || count > ctx->L - first)
-        return fail(ctx, DDP_EINVAL, w + ": layer range outside [0, " + std::to_string(ctx->L) + ")");
+        return fail(ctx, DDP_EINVAL, std::string(who) + ": layer range outside [0, " + std::to_string(ctx->L) + ")");
     if (ctx->dispatch_ways != 1 && !(first == 0 && count == ctx->L))
-        return fail(ctx, DDP_ESTATE, w + ": a layer range needs the update table in registration order (option dispatch_ways = 1)");
+        return fail(ctx, DDP_ESTATE, std::string(who) + ": a layer range needs the update table in registration order (option dispatch_ways = 1)");
     *c0 = ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)first]];
     *c1 = ctx->tensor_chunk_base[(size_t)ctx->layer_first_tensor[(size_t)(first + count)]];
     return DDP_OK;
@@ -630,9 +630,8 @@ static bool dense_range(const ddp_ctx *ctx, int first, int count, DenseLaunch &d
 }
 
 static int local_update_impl(ddp_ctx *ctx, const char *who, bool whole, int first, int count, const ddp_opt *opt, void *stream) {
-    const std::string w(who);
-    if (!ctx) return fail(nullptr, DDP_EINVAL, w + ": ctx is NULL");
-    if (!ctx->registered) return fail(ctx, DDP_ESTATE, w + ": no model registered");
+    if (!ctx) return fail(nullptr, DDP_EINVAL, std::string(who) + ": ctx is NULL");
+    if (!ctx->registered) return fail(ctx, DDP_ESTATE, std::string(who) + ": no model registered");
     UpdateScalars s{};
     int rc = make_scalars(ctx, who, opt, s);
     if (rc != DDP_OK) return rc;
@@ -670,8 +669,7 @@ static int fused_dense(ddp_ctx *ctx, const char *who, const SlotTables *st, cons
                        bool *done) {
     *done = false;
     if (!ctx->dense || !ctx->dense_path || !ctx->nontemporal || !fused_dense_supports(N)) return DDP_OK;
-    std::vector<int> pos((size_t)ctx->L, -1);  // layer -> position in the slot
-    for (size_t i = 0; i < st->layers.size(); ++i) pos[(size_t)st->layers[i]] = (int)i;
+    const std::vector<int32_t> &pos = st->layer_pos;  // layer -> position in the slot, -1 if not scheduled
     auto elem0 = [&](int l) { return ctx->tensor_elem_off[(size_t)ctx->layer_first_tensor[(size_t)l]]; };
     // every launch must start on a vector boundary in the model and, for a scheduled layer, in the flat buffer
     for (int l = first; l < first + count; ++l) {
@@ -734,16 +732,15 @@ static int fused_dense(ddp_ctx *ctx, const char *who, const SlotTables *st, cons
 static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, bool update_first, int slot, bool whole, int first, int count,
                       const void *const *peers, int N, int local_rank, double *layer_stats, const ddp_opt *opt, void *stream) {
     int rc;
-    const std::string w(who);
     const SlotTables *st = slot_of(ctx, slot, who, &rc);
     if (!st) return rc;
     UpdateScalars s{};
     if ((rc = make_scalars(ctx, who, opt, s)) != DDP_OK) return rc;
     if ((rc = check_device(ctx, who)) != DDP_OK) return rc;
-    if (N < 1 || N > DDP_MAX_REPLICAS) return fail(ctx, DDP_EINVAL, w + ": N must be in [1, " + std::to_string((int)DDP_MAX_REPLICAS) + "]");
-    if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, w + ": local_rank out of range");
-    if (N > 1 && !peers) return fail(ctx, DDP_EINVAL, w + ": peers is NULL");
-    if (layer_stats && !aligned(layer_stats, 8)) return fail(ctx, DDP_EALIGN, w + ": layer_stats must be 8-byte aligned");
+    if (N < 1 || N > DDP_MAX_REPLICAS) return fail(ctx, DDP_EINVAL, std::string(who) + ": N must be in [1, " + std::to_string((int)DDP_MAX_REPLICAS) + "]");
+    if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, std::string(who) + ": local_rank out of range");
+    if (N > 1 && !peers) return fail(ctx, DDP_EINVAL, std::string(who) + ": peers is NULL");
+    if (layer_stats && !aligned(layer_stats, 8)) return fail(ctx, DDP_EALIGN, std::string(who) + ": layer_stats must be 8-byte aligned");
     int64_t c0 = 0, c1 = ctx->n_update;
     if (!whole && (rc = layer_chunk_range(ctx, who, first, count, &c0, &c1)) != DDP_OK) return rc;
     FusedLaunch f{};

@@ -65,6 +65,7 @@ struct SlotTables {
     // dense arenas: per layer of the slot [first, last) index of its workgroups' partials (layers numbered in
     // registration order, ceil(layer elements / update_chunk) workgroups each)
     std::vector<int32_t> dense_ranges;
+    std::vector<int32_t> layer_pos;  // [L] layer -> position in this slot, -1 if not scheduled
     int32_t *d_dense_ranges = nullptr;
 };
 
