@@ -307,6 +307,14 @@ def test_small_llama_alg2_schedule_many_replicas(oracle):
     run_trajectory(oracle, W.small_llama(n_replicas=33, period=5), policy="alg2", iters=10)
 
 
+@pytest.mark.parametrize("fused,wire16", [(False, False), (True, False), (True, True)])
+def test_maximum_replica_count(oracle, fused, wire16):
+    # N = DDP_MAX_REPLICAS: the run-time replica loop at its limit, four calls and fused
+    from paper_2502_11058_amd import binding as B
+    t = run_trajectory(oracle, W.odd(n_replicas=B.DDP_MAX_REPLICAS, period=2), fused=fused, wire16=wire16, arena_offset=0)
+    assert t.frac() == 1.0
+
+
 def test_small_llama_bubble_filled_schedule(oracle):
     # Sec. 3.4: after filling, top layers sit in several slots; the comm-light synthetic times make filling happen
     w = W.small_llama()
