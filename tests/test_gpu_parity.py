@@ -315,6 +315,18 @@ def test_maximum_replica_count(oracle, fused, wire16):
     assert t.frac() == 1.0
 
 
+@pytest.mark.parametrize("fused", [False, True])
+def test_many_small_layers(oracle, fused):
+    # 240 layers of two small tensors each: long tables, one statistics row per layer, slots of 48 layers
+    ts = []
+    for l in range(240):
+        ts += [W.TensorSpec(f"l{l}.w", l, 64 * 64 + (l % 3)), W.TensorSpec(f"l{l}.b", l, 64)]
+    w = W.Workload("many_layers", ts, n_replicas=4, period=5, optimizer="adamw", param_dtype="bf16", lr=1e-3, sigma_drift=1e-4,
+                   sigma_grad=1e-3, iterations=6, policy="opt", time_noise=True)
+    t = run_trajectory(oracle, w, fused=fused)
+    assert t.frac() == 1.0
+
+
 def test_small_llama_bubble_filled_schedule(oracle):
     # Sec. 3.4: after filling, top layers sit in several slots; the comm-light synthetic times make filling happen
     w = W.small_llama()
