@@ -672,11 +672,16 @@ static int fused_dense(ddp_ctx *ctx, const char *who, const SlotTables *st, cons
     const std::vector<int32_t> &pos = st->layer_pos;  // layer -> position in the slot, -1 if not scheduled
     auto elem0 = [&](int l) { return ctx->tensor_elem_off[(size_t)ctx->layer_first_tensor[(size_t)l]]; };
     // every launch must start on a vector boundary in the model and, for a scheduled layer, in the flat buffer
+    int64_t launches = 0;
     for (int l = first; l < first + count; ++l) {
         const bool sched = pos[(size_t)l] >= 0, run_start = l == first || sched || pos[(size_t)l - 1] >= 0;
         if (run_start && elem0(l) % 4 != 0) return DDP_OK;
         if (sched && ((elem0(l + 1) - elem0(l)) % 4 != 0 || st->layer_begin[(size_t)pos[(size_t)l]] % 4 != 0)) return DDP_OK;
+        launches += run_start;
     }
+    // one launch per scheduled layer only pays when the launches are long: small layers stay with the single
+    // table-driven launch
+    if (launches > 1 && (elem0(first + count) - elem0(first)) / launches < (int64_t)1 << 18) return DDP_OK;
     *done = true;
     const bool stats = layer_stats != nullptr;
     int rc = 0;
