@@ -381,6 +381,11 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
             for (size_t i = 0; i + 1 < lcp.size(); ++i) {
                 mean_ranges.push_back(lcp[i]);
                 mean_ranges.push_back(lcp[i + 1]);
+                st.max_mean_partials = std::max<int64_t>(st.max_mean_partials, lcp[i + 1] - lcp[i]);
+            }
+            for (size_t i = 0; i + 1 < fused_ranges.size(); i += 2) {
+                st.max_fused_partials = std::max<int64_t>(st.max_fused_partials, fused_ranges[i + 1] - fused_ranges[i]);
+                st.max_dense_partials = std::max<int64_t>(st.max_dense_partials, st.dense_ranges[i + 1] - st.dense_ranges[i]);
             }
             if (rc == DDP_OK) rc = upload(ctx, mean_ranges, &st.d_layer_ranges);
             if (rc == DDP_OK) rc = upload(ctx, tflat, &st.d_tensor_flat_off);
@@ -535,6 +540,7 @@ static int partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int 
     a.slice_sums = ctx->d_slice_sums;
     a.layer_ranges = s->d_layer_ranges;
     a.n_layers = (int)s->layers.size();
+    a.max_partials_per_layer = s->max_mean_partials;
     a.stats = layer_stats;
     a.nontemporal = ctx->nontemporal;
     // bf16 replicas put half the bytes per workgroup in flight: half the pad, twice the workgroups per CU
@@ -726,7 +732,7 @@ static int fused_dense(ddp_ctx *ctx, const char *who, const SlotTables *st, cons
         int j = i + 1;
         while (j < nl && inside(j)) ++j;
         rc = launch_stats(ctx->d_partials, ctx->d_slice_sums + (int64_t)i * 2 * kStatSlices, st->d_dense_ranges + 2 * i, j - i, N,
-                          layer_stats + 2 * i, stream);
+                          layer_stats + 2 * i, st->max_dense_partials, stream);
         i = j;
     }
     return after_launch(ctx, who, rc);
@@ -782,6 +788,7 @@ static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, bool update_fi
     const int nl = (int)st->layers.size();
     if (!layer_stats || nl == 0) return after_launch(ctx, who, launch_fused(f, stream));
     f.partials = ctx->d_partials;
+    f.max_partials_per_layer = st->max_fused_partials;
     if (whole) {
         f.slice_sums = ctx->d_slice_sums;
         f.layer_ranges = st->d_fused_ranges;
@@ -807,7 +814,7 @@ static int fused_impl(ddp_ctx *ctx, const char *who, bool wire16, bool update_fi
             rc = launch_fused(f, stream);
             launched = true;
         } else {
-            rc = launch_stats(f.partials, f.slice_sums, f.layer_ranges, f.n_layers, N, f.stats, stream);
+            rc = launch_stats(f.partials, f.slice_sums, f.layer_ranges, f.n_layers, N, f.stats, f.max_partials_per_layer, stream);
         }
         if (rc != 0) return after_launch(ctx, who, rc);
         i = j;

@@ -65,6 +65,7 @@ struct SlotTables {
     // dense arenas: per layer of the slot [first, last) index of its workgroups' partials (layers numbered in
     // registration order, ceil(layer elements / update_chunk) workgroups each)
     std::vector<int32_t> dense_ranges;
+    int64_t max_mean_partials = 0, max_fused_partials = 0, max_dense_partials = 0;  // largest per-layer count of each range table
     std::vector<int32_t> layer_pos;  // [L] layer -> position in this slot, -1 if not scheduled
     int32_t *d_dense_ranges = nullptr;
 };
@@ -82,6 +83,7 @@ struct MeanLaunch {
     double *slice_sums;  // [n_layers][64][2] scratch of the two-stage reduction
     const int32_t *layer_ranges;  // per layer [first, last) partial index
     int n_layers;
+    int64_t max_partials_per_layer;
     double *stats;  // [n_layers][2]
     bool nontemporal;
     int lds_pad;
@@ -97,9 +99,12 @@ int launch_copy(bool unpack, const TensorDesc *tensors, const CopyChunk *chunks,
 int launch_mean(const MeanLaunch &a, void *stream);
 // Per-layer statistics from per-chunk partials: layer l of n_layers adds partials [ranges[2l], ranges[2l+1]) in a fixed
 // order through kStatSlices slice sums (slice_sums: [n_layers][kStatSlices][2]) into stats[2l], stats[2l+1].
+// With at most kStatSingleMax partials in any of the layers (max_partials_per_layer, an upper bound is enough) one launch
+// does it all; beyond that the two stages.
 constexpr int kStatSlices = 64;
+constexpr int64_t kStatSingleMax = 4096;
 int launch_stats(const double *partials, double *slice_sums, const int32_t *ranges, int n_layers, int n_replicas, double *stats,
-                 void *stream);
+                 int64_t max_partials_per_layer, void *stream);
 int launch_pack16(const TensorDesc *tensors, const CopyChunk *chunks, int64_t n_chunks, uint16_t *flat16, bool nontemporal, int lds_pad,
                   void *stream);
 struct FusedLaunch {
@@ -121,6 +126,7 @@ struct FusedLaunch {
     double *slice_sums;
     const int32_t *layer_ranges;
     int n_layers;
+    int64_t max_partials_per_layer;
     double *stats;
     int lds_pad;
 };

@@ -430,6 +430,26 @@ __global__ __launch_bounds__(kWave) void stats_finalize_kernel(const double *__r
     }
 }
 
+// The same reduction in one launch, for layers with few partials (launch-bound slots): one workgroup per layer adds the
+// layer's partials thread-strided, then the workgroup tree.  Fixed order as well.
+__global__ __launch_bounds__(kThreads) void stats_single_kernel(const double *__restrict__ partials, const int32_t *__restrict__ ranges,
+                                                                int n_replicas, double *__restrict__ stats) {
+    __shared__ double lds[2][kThreads / kWave];
+    const int l = blockIdx.x;
+    const int64_t c0 = ranges[2 * l], c1 = ranges[2 * l + 1];
+    double g = 0.0, m = 0.0;
+    for (int64_t c = c0 + (int64_t)threadIdx.x; c < c1; c += kThreads) {
+        g += partials[2 * c];
+        m += partials[2 * c + 1];
+    }
+    g = block_sum(g, lds[0]);
+    m = block_sum(m, lds[1]);
+    if (threadIdx.x == 0) {
+        stats[2 * l] = g / (double)n_replicas;
+        stats[2 * l + 1] = m;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------------
 // local update
 // ---------------------------------------------------------------------------------------------------------------
@@ -1021,8 +1041,13 @@ int launch_mean_n(const MeanArgs &ma, const MeanLaunch &a, void *stream) {
 }  // namespace
 
 int launch_stats(const double *partials, double *slice_sums, const int32_t *ranges, int n_layers, int n_replicas, double *stats,
-                 void *stream) {
+                 int64_t max_partials_per_layer, void *stream) {
     if (n_layers <= 0) return 0;
+    if (max_partials_per_layer <= kStatSingleMax) {
+        hipLaunchKernelGGL(stats_single_kernel, dim3((unsigned)n_layers), dim3(kThreads), 0, (hipStream_t)stream, partials, ranges,
+                           n_replicas, stats);
+        return (int)hipGetLastError();
+    }
     hipLaunchKernelGGL(stats_slices_kernel, dim3(kStatSlices, (unsigned)n_layers), dim3(kThreads), 0, (hipStream_t)stream, partials,
                        ranges, slice_sums);
     hipError_t e = hipGetLastError();
@@ -1079,7 +1104,7 @@ int launch_mean(const MeanLaunch &a, void *stream) {
         }
     }
     if (rc != 0 || !a.partials) return rc;
-    return launch_stats(a.partials, a.slice_sums, a.layer_ranges, a.n_layers, a.n_replicas, a.stats, stream);
+    return launch_stats(a.partials, a.slice_sums, a.layer_ranges, a.n_layers, a.n_replicas, a.stats, a.max_partials_per_layer, stream);
 }
 
 int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *tensors, const UpdateChunk *chunks, int64_t n_chunks,
@@ -1238,7 +1263,7 @@ int launch_fused(const FusedLaunch &f, void *stream) {
     DDP_F(true, true, true)
 #undef DDP_F
     if (rc != 0 || !f.partials) return rc;
-    return launch_stats(f.partials, f.slice_sums, f.layer_ranges, f.n_layers, f.n_replicas, f.stats, stream);
+    return launch_stats(f.partials, f.slice_sums, f.layer_ranges, f.n_layers, f.n_replicas, f.stats, f.max_partials_per_layer, stream);
 }
 
 }  // namespace ddp
