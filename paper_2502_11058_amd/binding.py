@@ -197,6 +197,18 @@ def _dev_ptrs(tensors) -> "C.Array":
     return arr
 
 
+def device_pointer_array(tensors) -> "C.Array":
+    """The host array of device pointers that the peers arguments take, built once; a caller that passes the same
+    buffers every iteration hands this to the entry points instead of the list of tensors."""
+    return _dev_ptrs(list(tensors))
+
+
+def _peers_arg(peers):
+    if not peers:
+        return None
+    return peers if isinstance(peers, C.Array) else _dev_ptrs(list(peers))
+
+
 class Context:
     """Owns a ddp_ctx.  Methods carry the names of the C entry points and only marshal arguments."""
 
@@ -268,7 +280,7 @@ class Context:
         _check(lib().ddp_pack(self._h, slot, flat_local.data_ptr(), _stream_handle(stream)), self._h)
 
     def ddp_partial_average(self, slot: int, flat_local, peers, N: int, local_rank: int, flat_out, layer_stats=None, stream=None) -> None:
-        arr = _dev_ptrs(list(peers)) if peers else None
+        arr = _peers_arg(peers)
         _check(lib().ddp_partial_average(self._h, slot, flat_local.data_ptr(), None if arr is None else C.addressof(arr), N, local_rank,
                                          flat_out.data_ptr(), None if layer_stats is None else layer_stats.data_ptr(),
                                          _stream_handle(stream)), self._h)
@@ -280,7 +292,7 @@ class Context:
         _check(lib().ddp_local_update(self._h, C.byref(opt), _stream_handle(stream)), self._h)
 
     def ddp_fused_sync_update(self, slot: int, peers, N: int, local_rank: int, layer_stats, opt: ddp_opt, stream=None) -> None:
-        arr = _dev_ptrs(list(peers)) if peers else None
+        arr = _peers_arg(peers)
         _check(lib().ddp_fused_sync_update(self._h, slot, None if arr is None else C.addressof(arr), N, local_rank,
                                            None if layer_stats is None else layer_stats.data_ptr(), C.byref(opt),
                                            _stream_handle(stream)), self._h)
@@ -290,13 +302,13 @@ class Context:
 
     def ddp_partial_average_wire16(self, slot: int, flat_local16, peers16, N: int, local_rank: int, flat_out, layer_stats=None,
                                    stream=None) -> None:
-        arr = _dev_ptrs(list(peers16)) if peers16 else None
+        arr = _peers_arg(peers16)
         _check(lib().ddp_partial_average_wire16(self._h, slot, flat_local16.data_ptr(), None if arr is None else C.addressof(arr), N,
                                                 local_rank, flat_out.data_ptr(),
                                                 None if layer_stats is None else layer_stats.data_ptr(), _stream_handle(stream)), self._h)
 
     def ddp_fused_sync_update_wire16(self, slot: int, peers16, N: int, local_rank: int, layer_stats, opt: ddp_opt, stream=None) -> None:
-        arr = _dev_ptrs(list(peers16)) if peers16 else None
+        arr = _peers_arg(peers16)
         _check(lib().ddp_fused_sync_update_wire16(self._h, slot, None if arr is None else C.addressof(arr), N, local_rank,
                                                   None if layer_stats is None else layer_stats.data_ptr(), C.byref(opt),
                                                   _stream_handle(stream)), self._h)
@@ -306,7 +318,7 @@ class Context:
 
     def ddp_fused_sync_update_layers(self, slot: int, layer_first: int, layer_count: int, peers, wire_dtype: int, order: int, N: int,
                                      local_rank: int, layer_stats, opt: ddp_opt, stream=None) -> None:
-        arr = _dev_ptrs(list(peers)) if peers else None
+        arr = _peers_arg(peers)
         _check(lib().ddp_fused_sync_update_layers(self._h, slot, layer_first, layer_count, None if arr is None else C.addressof(arr),
                                                   wire_dtype, order, N, local_rank,
                                                   None if layer_stats is None else layer_stats.data_ptr(), C.byref(opt),

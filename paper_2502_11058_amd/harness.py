@@ -184,6 +184,9 @@ class DeviceReplica:
         self.peers = [region(f"peer{k}") for k in range(n_peers)]
         self.flat16 = region("flat16")
         self.peers16 = [region(f"peer16_{k}") for k in range(n_peers)] if self.wire16 else []
+        # the pointer arrays the entry points take, marshalled once
+        self._peers_arr = B.device_pointer_array(self.peers) if self.peers else None
+        self._peers16_arr = B.device_pointer_array(self.peers16) if self.peers16 else None
         self.offsets = np.concatenate([[0], np.cumsum(self.numel)]).astype(np.int64) + o
 
         def views(a):
@@ -246,13 +249,13 @@ class DeviceReplica:
         c = self.ctx
         if wire16:
             c.ddp_pack_wire16(slot, self.flat16, stream)
-            c.ddp_partial_average_wire16(slot, self.flat16, self.peers16, len(self.peers16) + 1, local_rank, self.flat,
+            c.ddp_partial_average_wire16(slot, self.flat16, self._peers16_arr, len(self.peers16) + 1, local_rank, self.flat,
                                          self.stats if with_stats else None, stream)
             c.ddp_unpack(slot, self.flat, stream)
             c.ddp_local_update(self.opt_struct(r + 1), stream)
             return
         c.ddp_pack(slot, self.flat, stream)
-        c.ddp_partial_average(slot, self.flat, self.peers, len(self.peers) + 1, local_rank, self.flat,
+        c.ddp_partial_average(slot, self.flat, self._peers_arr, len(self.peers) + 1, local_rank, self.flat,
                               self.stats if with_stats else None, stream)
         c.ddp_unpack(slot, self.flat, stream)
         c.ddp_local_update(self.opt_struct(r + 1), stream)
@@ -268,10 +271,10 @@ class DeviceReplica:
                                                   self.opt_struct(r + 1), stream)
             return
         if wire16:
-            self.ctx.ddp_fused_sync_update_wire16(slot, self.peers16, len(self.peers16) + 1, local_rank,
+            self.ctx.ddp_fused_sync_update_wire16(slot, self._peers16_arr, len(self.peers16) + 1, local_rank,
                                                   self.stats if with_stats else None, self.opt_struct(r + 1), stream)
             return
-        self.ctx.ddp_fused_sync_update(slot, self.peers, len(self.peers) + 1, local_rank, self.stats if with_stats else None,
+        self.ctx.ddp_fused_sync_update(slot, self._peers_arr, len(self.peers) + 1, local_rank, self.stats if with_stats else None,
                                        self.opt_struct(r + 1), stream)
 
     def layerwise_step(self, r: int, side_stream, backward=None, bucket: int = 1, local_rank: int = 0, with_stats: bool = True,
