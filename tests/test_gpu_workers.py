@@ -118,3 +118,42 @@ def test_eight_workers_update_then_sync_with_bubble_filling(oracle):
     w = W.small_llama(n_blocks=6, n_replicas=8, period=4)
     agreed = run_workers(oracle, w, K=8, iters=8, mode="calls", order=1, policy="enp+fill")
     assert agreed.min() >= 2                              # filled layers are synchronised more than once per period
+
+
+def test_two_contexts_on_two_streams_do_not_interfere():
+    # contexts own their tables and reduction scratch: two workers stepping at the same time on their own streams
+    # end with the bits they get when they run one after the other
+    from paper_2502_11058_amd.harness import DeviceReplica
+    assert torch.cuda.is_available(), "no GPU visible: the HIP path cannot run (there is no CPU fallback)"
+    w = W.small_llama(n_replicas=4, period=2)
+
+    def make(worker):
+        rep = DeviceReplica(w, 0)
+        rep.init_params()
+        rep.ctx.ddp_pack(0, rep.flat)
+        torch.cuda.synchronize()
+        rep.fill_peers_from(rep.flat, worker, rep.flat.numel())
+        return rep
+
+    together = [make(0), make(1)]
+    apart = [make(0), make(1)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for r in range(6):
+        for k in range(2):
+            together[k].fill_grads(r, worker=k)
+            apart[k].fill_grads(r, worker=k)
+        torch.cuda.synchronize()
+        for k in range(2):                                   # both in flight at once, fused and four-call alternating
+            with torch.cuda.stream(streams[k]):
+                (together[k].fused_step if (r + k) % 2 else together[k].step)(r, local_rank=k, stream=streams[k])
+        for k in range(2):
+            (apart[k].fused_step if (r + k) % 2 else apart[k].step)(r, local_rank=k)
+            torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        for k in range(2):
+            for x, y in ((together[k].a_sync, apart[k].a_sync), (together[k].a_s0, apart[k].a_s0), (together[k].a_s1, apart[k].a_s1)):
+                assert torch.equal(x.view(torch.int32), y.view(torch.int32)), f"worker {k} r={r}"
+            assert torch.equal(together[k].a_model.view(torch.int16), apart[k].a_model.view(torch.int16))
+            assert torch.equal(together[k].stats, apart[k].stats)
+    for rep in together + apart:
+        rep.close()
