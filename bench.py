@@ -159,7 +159,8 @@ def main() -> int:
         import gc
         res = []
         for _ in range(args.placement_study):
-            rep = DeviceReplica(w, 0, options=options, policy=args.policy, placement_probe=False)
+            rep = DeviceReplica(w, 0, options=options, policy=args.policy, placement_probe=False,
+                                front_pad=(args.front_pad_gib or 0) << 30)
             res.append(round(rep._probe(), 1))
             rep.close()
             rep._release()
@@ -167,7 +168,7 @@ def main() -> int:
             del rep
             gc.collect()
             torch.cuda.empty_cache()
-        print(json.dumps({"placement_study_update_GBps": res, "workload": w.name}))
+        print(json.dumps({"placement_study_update_GBps": res, "workload": w.name, "front_pad_GiB": args.front_pad_gib or 0}))
         return 0
     if args.front_pad_gib is None:
         rep = DeviceReplica(w, 0, options=options, policy=args.policy, wire16=args.wire16,
