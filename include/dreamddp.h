@@ -194,10 +194,18 @@ int ddp_unpack(ddp_ctx *ctx, int slot, const float *flat, void *stream);
 
 /* Eq. (5), first case (Algorithm 1 "update model") with the optimizers of the paper's experiments.
  * kind DDP_OPT_SGDM:  buf = momentum*buf + g;  p = p - lr*buf
- * kind DDP_OPT_ADAMW: m = beta1*m + (1-beta1)*g;  v = beta2*v + ((1-beta2)*g)*g;  p = p*(1 - lr*weight_decay);
- *                     p = p - (lr/(1-beta1^step)) * ( m / (sqrt(v)/sqrt(1-beta2^step) + eps) )
- * step is 1-based.  Every product and sum is a separate fp32 operation; bf16 gradients are widened exactly;
- * the bf16 model copy, if registered, is rewritten from the new p by round-to-nearest-even.
+ * kind DDP_OPT_ADAMW (decoupled weight decay, bias-corrected moments), exactly this sequence of fp32 operations:
+ *     per call, on the host:  bc1 = 1 - beta1^step and bc2 = 1 - beta2^step in fp64;
+ *                             step_size = lr * fp32(1/bc1)   (the reciprocal rounded to fp32, then one fp32 product)
+ *                             rs2       = fp32(1/sqrt(bc2))  (computed in fp64, rounded to fp32 once)
+ *                             decay     = 1 - lr*weight_decay,  omb1 = 1 - beta1,  omb2 = 1 - beta2   (fp32)
+ *     per element:            m = beta1*m + omb1*g;   v = beta2*v + (omb2*g)*g;   p = p*decay;
+ *                             p = p - step_size * ( m / (sqrt(v)*rs2 + eps) )
+ *   i.e. the bias corrections enter as multiplications by rounded reciprocals, not as the divisions
+ *   m/bc1 and sqrt(v)/sqrt(bc2) of the textbook form; the two forms agree to a few fp32 ulps per step, not bit for bit.
+ *   sqrt and the division are the correctly rounded IEEE operations.
+ * step is 1-based.  Every product and sum is a separate fp32 operation (no fused multiply-add); bf16 gradients are
+ * widened exactly; the bf16 model copy, if registered, is rewritten from the new p by round-to-nearest-even.
  * Applies to every registered tensor. */
 typedef struct {
     int32_t kind;

@@ -120,21 +120,6 @@ static bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintp
 
 using namespace ddp;
 
-// No C++ exception crosses the C boundary: the per-iteration entry points build messages and small host vectors, so a
-// failed host allocation is turned into DDP_ENOMEM here (the message itself may then be empty).
-template <class F>
-static int guarded(const ddp_ctx *ctx, F &&body) noexcept {
-    try {
-        return body();
-    } catch (...) {
-        try {
-            return fail(ctx, DDP_ENOMEM, "host allocation failed");
-        } catch (...) {
-            return DDP_ENOMEM;
-        }
-    }
-}
-
 extern "C" const char *ddp_last_error(const ddp_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
 
 extern "C" int ddp_create(ddp_ctx **out, int device) {
@@ -290,8 +275,8 @@ extern "C" int ddp_register_model(ddp_ctx *ctx, int L, int T, const int32_t *lay
         ctx->n_update = (int64_t)uc.size();
         ctx->registered = true;
         return DDP_OK;
-    } catch (const std::exception &e) {
-        return fail(ctx, DDP_ENOMEM, std::string("ddp_register_model: host allocation failed: ") + e.what());
+    } catch (...) {
+        return fail_nothrow(ctx, DDP_ENOMEM, "ddp_register_model: host allocation failed");
     }
 }
 
@@ -410,8 +395,8 @@ extern "C" int ddp_set_schedule(ddp_ctx *ctx, int H, const int32_t *set_ptr, con
         ctx->slots = std::move(slots);
         ctx->H = H;
         return DDP_OK;
-    } catch (const std::exception &e) {
-        return fail(ctx, DDP_ENOMEM, std::string("ddp_set_schedule: host allocation failed: ") + e.what());
+    } catch (...) {
+        return fail_nothrow(ctx, DDP_ENOMEM, "ddp_set_schedule: host allocation failed");
     }
 }
 
@@ -497,11 +482,24 @@ extern "C" int ddp_unpack(ddp_ctx *ctx, int slot, const float *flat, void *strea
 
 // Shared body of the two averaging entry points; `who` names the caller in messages.  wire16: the replicas are
 // bf16 buffers (2 bytes per element) and the output is a separate fp32 buffer.
-static int partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, const void *flat_local, const void *const *peers,
-                                int N, int local_rank, float *flat_out, double *layer_stats, void *stream) {
+// scratch: where the per-chunk partial sums and the slice sums of the statistics go (nullptr: the context's own
+// reduction scratch), scratch_bytes: its size.
+int ddp::partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, const void *flat_local, const void *const *peers,
+                              int N, int local_rank, float *flat_out, double *layer_stats, void *stream, double *scratch,
+                              int64_t scratch_bytes) {
     int rc;
     const SlotTables *s = slot_of(ctx, slot, who, &rc);
     if (!s) return rc;
+    double *partials = ctx->d_partials, *slice_sums = ctx->d_slice_sums;
+    if (scratch) {
+        const int64_t need = (s->n_mean + (int64_t)s->layers.size() * kStatSlices) * 2 * (int64_t)sizeof(double);
+        if (layer_stats && need > scratch_bytes)
+            return fail(ctx, DDP_ESHAPE, std::string(who) + ": slot " + std::to_string(slot) + " needs " + std::to_string(need) +
+                                             " bytes of reduction scratch (" + std::to_string(s->n_mean) + " chunks), the fixed scratch holds " +
+                                             std::to_string(scratch_bytes) + "; use ddp_partial_average or a larger mean_chunk");
+        partials = scratch;
+        slice_sums = scratch + 2 * s->n_mean;
+    }
     if ((rc = check_device(ctx, who)) != DDP_OK) return rc;
     if (N < 1 || N > DDP_MAX_REPLICAS) return fail(ctx, DDP_EINVAL, std::string(who) + ": N must be in [1, " + std::to_string((int)DDP_MAX_REPLICAS) + "]");
     if (local_rank < 0 || local_rank >= N) return fail(ctx, DDP_EINVAL, std::string(who) + ": local_rank out of range");
@@ -536,8 +534,8 @@ static int partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int 
     a.out = flat_out;
     a.chunks = s->d_mean;
     a.n_chunks = s->n_mean;
-    a.partials = layer_stats ? ctx->d_partials : nullptr;
-    a.slice_sums = ctx->d_slice_sums;
+    a.partials = layer_stats ? partials : nullptr;
+    a.slice_sums = slice_sums;
     a.layer_ranges = s->d_layer_ranges;
     a.n_layers = (int)s->layers.size();
     a.max_partials_per_layer = s->max_mean_partials;
@@ -553,7 +551,7 @@ extern "C" int ddp_partial_average(ddp_ctx *ctx, int slot, const float *flat_loc
                                    int local_rank, float *flat_out, double *layer_stats, void *stream) {
     return guarded(ctx, [&]() -> int {
         return partial_average_impl(ctx, "ddp_partial_average", false, slot, flat_local, reinterpret_cast<const void *const *>(peers), N,
-                                    local_rank, flat_out, layer_stats, stream);
+                                    local_rank, flat_out, layer_stats, stream, nullptr, 0);
     });
 }
 
@@ -574,7 +572,7 @@ extern "C" int ddp_partial_average_wire16(ddp_ctx *ctx, int slot, const uint16_t
                                           int local_rank, float *flat_out, double *layer_stats, void *stream) {
     return guarded(ctx, [&]() -> int {
         return partial_average_impl(ctx, "ddp_partial_average_wire16", true, slot, flat_local16,
-                                    reinterpret_cast<const void *const *>(peers16), N, local_rank, flat_out, layer_stats, stream);
+                                    reinterpret_cast<const void *const *>(peers16), N, local_rank, flat_out, layer_stats, stream, nullptr, 0);
     });
 }
 

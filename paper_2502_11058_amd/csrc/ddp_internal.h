@@ -13,6 +13,26 @@ namespace ddp {
 // Record a failure message (on the context, or thread-local when ctx is NULL) and return the code.
 int fail(const ddp_ctx *ctx, int code, const std::string &msg);
 
+// The same from a catch block: if recording the message throws as well, the code alone is returned.
+inline int fail_nothrow(const ddp_ctx *ctx, int code, const char *msg) noexcept {
+    try {
+        return fail(ctx, code, msg);
+    } catch (...) {
+        return code;
+    }
+}
+
+// No C++ exception crosses the C boundary: the entry points build messages and small host vectors, so a failed host
+// allocation (or anything else thrown) is turned into DDP_ENOMEM here.
+template <class F>
+int guarded(const ddp_ctx *ctx, F &&body) noexcept {
+    try {
+        return body();
+    } catch (...) {
+        return fail_nothrow(ctx, DDP_ENOMEM, "host allocation failed");
+    }
+}
+
 // ---- device tables -------------------------------------------------------------------------------------------
 // Everything a kernel needs to find its work is in small read-only tables in HBM, built once when the model
 // is registered or the schedule installed.  One workgroup handles one "chunk": a run of elements that lies
@@ -163,6 +183,10 @@ bool fused_dense_supports(int n_replicas);
 int launch_fused_dense(const FusedDenseLaunch &f, void *stream);
 int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *tensors, const UpdateChunk *chunks,
                   int64_t n_chunks, const UpdateScalars &s, bool nontemporal, int lds_pad, void *stream);
+
+// Shared body of the averaging entry points (ddp_context.hip).  scratch == nullptr: the context's reduction scratch.
+int partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, const void *flat_local, const void *const *peers, int N,
+                         int local_rank, float *flat_out, double *layer_stats, void *stream, double *scratch, int64_t scratch_bytes);
 
 }  // namespace ddp
 
