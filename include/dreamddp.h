@@ -272,6 +272,22 @@ int ddp_fused_sync_update_layers(ddp_ctx *ctx, int slot, int layer_first, int la
                                  int wire_dtype, int order, int N, int local_rank, double *layer_stats, const ddp_opt *opt,
                                  void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): ddp_partial_average with its reduction scratch (one pair of fp64 partial sums per chunk of
+ * mean_chunk elements, then 64 slice sums per layer of the slot) in a fixed array of DDP_STATIC_SCRATCH_BYTES inside the
+ * library's device image, one copy per GPU, instead of memory owned by the context.  Same arguments, same kernels and
+ * bit for bit the same flat_out and layer_stats as ddp_partial_average.  Neither this call nor anything it calls
+ * allocates or frees device or pinned memory; the device address of the array is resolved once per device in ddp_create.
+ *   - A slot whose statistics need more than the fixed array (more than about 2^20 chunks: 2.1 G elements at the default
+ *     mean_chunk) is rejected with DDP_ESHAPE before anything is launched; with layer_stats == NULL any size passes,
+ *     since the scratch is then not used.
+ *   - Every call on a GPU, from any context or thread, shares that GPU's array: calls that may overlap in time on one GPU
+ *     (different streams, different contexts) race on it and must be ordered by the caller.  The array keeps the last
+ *     call's contents; nothing in it has to start at zero, because every partial a call reads it has written before. */
+enum { DDP_STATIC_SCRATCH_BYTES = 16 << 20 };
+int ddp_partial_average_static(ddp_ctx *ctx, int slot, const float *flat_local, const float *const *peers, int N,
+                               int local_rank, float *flat_out, double *layer_stats, void *stream);
+
 /* Message of the last failure on this context (ctx == NULL: last failure of ddp_create / ddp_schedule* in
  * this thread).  Never NULL; valid until the next call on the same context / thread. */
 const char *ddp_last_error(const ddp_ctx *ctx);

@@ -18,6 +18,7 @@ DDP_F32, DDP_BF16 = 0, 1
 DDP_OPT_SGDM, DDP_OPT_ADAMW = 0, 1
 DDP_SYNC_THEN_UPDATE, DDP_UPDATE_THEN_SYNC = 0, 1
 DDP_MAX_REPLICAS = 64
+DDP_STATIC_SCRATCH_BYTES = 16 << 20
 POLICIES = {"enp": 0, "round_robin": 1, "full": 2, "every": 3, "opt": 4, "alg2": 5}
 STATUS = {0: "DDP_OK", 1: "DDP_EINVAL", 2: "DDP_ESHAPE", 3: "DDP_EALIGN", 4: "DDP_ENOMEM", 5: "DDP_EHIP", 6: "DDP_ESCHED",
           7: "DDP_ESTATE"}
@@ -27,7 +28,7 @@ EXPORTS = [
     "ddp_register_model", "ddp_set_schedule", "ddp_slot_numel", "ddp_slot_num_layers", "ddp_slot_num_tensors",
     "ddp_slot_layout", "ddp_pack", "ddp_partial_average", "ddp_unpack", "ddp_local_update", "ddp_fused_sync_update",
     "ddp_pack_wire16", "ddp_partial_average_wire16", "ddp_fused_sync_update_wire16",
-    "ddp_local_update_layers", "ddp_fused_sync_update_layers", "ddp_last_error",
+    "ddp_local_update_layers", "ddp_fused_sync_update_layers", "ddp_partial_average_static", "ddp_last_error",
 ]
 
 
@@ -70,6 +71,7 @@ def lib():
         l.ddp_pack.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         l.ddp_unpack.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         l.ddp_partial_average.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.ddp_partial_average_static.argtypes = l.ddp_partial_average.argtypes
         l.ddp_local_update.argtypes = [C.c_void_p, C.POINTER(ddp_opt), C.c_void_p]
         l.ddp_fused_sync_update.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.POINTER(ddp_opt), C.c_void_p]
         l.ddp_pack_wire16.argtypes = l.ddp_pack.argtypes
@@ -284,6 +286,13 @@ class Context:
         _check(lib().ddp_partial_average(self._h, slot, flat_local.data_ptr(), None if arr is None else C.addressof(arr), N, local_rank,
                                          flat_out.data_ptr(), None if layer_stats is None else layer_stats.data_ptr(),
                                          _stream_handle(stream)), self._h)
+
+    def ddp_partial_average_static(self, slot: int, flat_local, peers, N: int, local_rank: int, flat_out, layer_stats=None,
+                                   stream=None) -> None:
+        arr = _peers_arg(peers)
+        _check(lib().ddp_partial_average_static(self._h, slot, flat_local.data_ptr(), None if arr is None else C.addressof(arr), N,
+                                                local_rank, flat_out.data_ptr(),
+                                                None if layer_stats is None else layer_stats.data_ptr(), _stream_handle(stream)), self._h)
 
     def ddp_unpack(self, slot: int, flat, stream=None) -> None:
         _check(lib().ddp_unpack(self._h, slot, flat.data_ptr(), _stream_handle(stream)), self._h)

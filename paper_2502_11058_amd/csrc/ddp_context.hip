@@ -134,6 +134,12 @@ extern "C" int ddp_create(ddp_ctx **out, int device) {
     ddp_ctx *c = new (std::nothrow) ddp_ctx();
     if (!c) return fail(nullptr, DDP_ENOMEM, "ddp_create: out of host memory");
     c->device = device;
+    // the device address of the library's fixed scratch array, resolved here once per device (the device is current)
+    int rc = static_scratch_for(nullptr, device, &c->static_scratch);
+    if (rc != DDP_OK) {
+        delete c;
+        return rc;
+    }
     *out = c;
     return DDP_OK;
 }

@@ -188,6 +188,10 @@ int launch_update(int kind, int grad_dtype, bool with_model, const TensorDesc *t
 int partial_average_impl(ddp_ctx *ctx, const char *who, bool wire16, int slot, const void *flat_local, const void *const *peers, int N,
                          int local_rank, float *flat_out, double *layer_stats, void *stream, double *scratch, int64_t scratch_bytes);
 
+// The fixed reduction scratch of ddp_partial_average_static on the current device (ddp_noalloc.hip): resolves the
+// device address of the library's static array once per device.  Call with `device` current.
+int static_scratch_for(const ddp_ctx *ctx, int device, double **ptr);
+
 }  // namespace ddp
 
 struct ddp_ctx {
@@ -221,6 +225,7 @@ struct ddp_ctx {
     double *d_partials = nullptr;  // reduction scratch for per-layer statistics: one partial pair per chunk ...
     double *d_slice_sums = nullptr;  // ... followed by 64 slice sums per layer (same allocation)
     int64_t partials_cap = 0;
+    double *static_scratch = nullptr;  // this device's copy of the library's fixed scratch array (ddp_partial_average_static)
 };
 
 #endif
