@@ -87,31 +87,44 @@ std::vector<int> solve_opt(const Instance &in) {
     return cut;
 }
 
-// Algorithm 2 without recursion.  A frame is a partial solution: the cut so far (cut[0..h] fixed, set h open
-// and starting at cut[h]), and the next position to place.  Frames are taken from a stack, and a search step
-// pushes the "delay" continuation before going on with "assign", so solutions are visited in the order of the
-// recursive formulation with the assign-branch first and "first minimum found" picks the same solution.
+// Algorithm 2 without recursion.  The search walks one partial solution at a time: cut[0..h] fixed, set h open and
+// starting at cut[h], `pos` the next position to place.  Where neither property decides, the "delay" continuation
+// (pos, h + 1) goes on a stack and the walk goes on with "assign"; a continuation taken from the stack re-opens set
+// h + 1 at pos.  Everything below index h + 1 of `cut` is still what it was when the continuation was pushed, because
+// the walk in between only ever wrote entries above h.  Solutions are therefore visited in the order of the recursive
+// formulation with the assign-branch first, and "first minimum found" picks the same solution.
+//
+// The solution set can grow exponentially with min(L, H) (Sec. 3.3 bounds it by a power of two): the walk stops after
+// kAlg2StepBudget placement steps and reports that, so that no instance can hold the caller for long.
+constexpr int64_t kAlg2StepBudget = 50'000'000;
+
 struct Alg2Result {
     std::vector<int> best;
     int64_t best_cost = -1;
     int64_t n_solutions = 0;
+    bool exhausted = false;  // the step budget ran out before the search was complete
 };
 
-Alg2Result solve_alg2(const Instance &in) {
+Alg2Result solve_alg2(const Instance &in, int64_t step_budget = kAlg2StepBudget) {
     const int L = in.L, H = in.H;
-    struct Frame {
-        int pos, h;
-        std::vector<int> cut;
+    struct Delayed {
+        int pos, h;  // set h opens at position pos
     };
     Alg2Result res;
-    std::vector<Frame> stack;
-    stack.push_back({0, 0, std::vector<int>(H + 1, 0)});
+    std::vector<int> cut(H + 1, 0);
+    std::vector<Delayed> stack;
+    stack.push_back({0, 0});
+    int64_t steps = 0;
     while (!stack.empty()) {
-        Frame fr = std::move(stack.back());
+        const Delayed fr = stack.back();
         stack.pop_back();
         int pos = fr.pos, h = fr.h;
-        std::vector<int> &cut = fr.cut;
+        cut[h] = pos;
         for (;;) {
+            if (++steps > step_budget) {
+                res.exhausted = true;
+                return res;
+            }
             if (pos == L || h == H - 1) {
                 // every layer placed (later sets stay empty), or the last set takes all that is left
                 for (int k = h + 1; k <= H; ++k) cut[k] = L;
@@ -137,14 +150,18 @@ Alg2Result solve_alg2(const Instance &in) {
                 cut[h + 1] = pos;
                 ++h;
             } else {  // neither property decides: keep "delay" for later, go on with "assign"
-                Frame delayed{pos, h + 1, cut};
-                delayed.cut[h + 1] = pos;
-                stack.push_back(std::move(delayed));
+                stack.push_back({pos, h + 1});
                 ++pos;
             }
         }
     }
     return res;
+}
+
+int alg2_exhausted(const char *who) {
+    return ddp::fail(nullptr, DDP_ESCHED, std::string(who) + ": Algorithm 2's search exceeded " + std::to_string(kAlg2StepBudget) +
+                                              " steps on this instance (its solution set grows exponentially); use DDP_SCHED_OPT, the exact "
+                                              "O(L^2 H) optimum of the same objective");
 }
 
 void emit_cut(int L, int H, const std::vector<int> &cut, int32_t *out_slot, int32_t *out_set_ptr, int32_t *out_set_layers) {
@@ -208,13 +225,15 @@ extern "C" int ddp_schedule(int policy, int L, int H, const int64_t *t_fp_ns, co
         } else if (policy == DDP_SCHED_OPT) {
             cut = solve_opt(in);
         } else {
-            cut = solve_alg2(in).best;
+            Alg2Result r = solve_alg2(in);
+            if (r.exhausted) return alg2_exhausted("ddp_schedule");
+            cut = std::move(r.best);
         }
         emit_cut(L, H, cut, out_slot, out_set_ptr, out_set_layers);
         if (out_cost_ns && have_times) *out_cost_ns = cost_of_cuts(in, cut);
         return DDP_OK;
-    } catch (const std::exception &e) {
-        return ddp::fail(nullptr, DDP_ENOMEM, std::string("ddp_schedule: host allocation failed: ") + e.what());
+    } catch (...) {
+        return ddp::fail_nothrow(nullptr, DDP_ENOMEM, "ddp_schedule: host allocation failed");
     }
 }
 
@@ -237,8 +256,8 @@ extern "C" int ddp_schedule_cost(int L, int H, const int64_t *t_bp_ns, const int
                 return ddp::fail(nullptr, DDP_ESCHED, "ddp_schedule_cost: sets are not a cut of the BP-ordered layer sequence");
         *out_cost_ns = cost_of_cuts(in, cut);
         return DDP_OK;
-    } catch (const std::exception &e) {
-        return ddp::fail(nullptr, DDP_ENOMEM, std::string("ddp_schedule_cost: host allocation failed: ") + e.what());
+    } catch (...) {
+        return ddp::fail_nothrow(nullptr, DDP_ENOMEM, "ddp_schedule_cost: host allocation failed");
     }
 }
 
@@ -249,10 +268,12 @@ extern "C" int ddp_schedule_alg2_solutions(int L, int H, const int64_t *t_bp_ns,
         Instance in;
         int rc = make_instance(L, H, t_bp_ns, t_comm_ns, in);
         if (rc != DDP_OK) return rc;
-        *out_count = solve_alg2(in).n_solutions;
+        const Alg2Result r = solve_alg2(in);
+        if (r.exhausted) return alg2_exhausted("ddp_schedule_alg2_solutions");
+        *out_count = r.n_solutions;
         return DDP_OK;
-    } catch (const std::exception &e) {
-        return ddp::fail(nullptr, DDP_ENOMEM, std::string("ddp_schedule_alg2_solutions: host allocation failed: ") + e.what());
+    } catch (...) {
+        return ddp::fail_nothrow(nullptr, DDP_ENOMEM, "ddp_schedule_alg2_solutions: host allocation failed");
     }
 }
 
@@ -301,8 +322,8 @@ extern "C" int ddp_schedule_fill_bubbles(int L, int H, const int64_t *t_bp_ns, c
         }
         out_set_ptr[H] = n;
         return DDP_OK;
-    } catch (const std::exception &e) {
-        return ddp::fail(nullptr, DDP_ENOMEM, std::string("ddp_schedule_fill_bubbles: host allocation failed: ") + e.what());
+    } catch (...) {
+        return ddp::fail_nothrow(nullptr, DDP_ENOMEM, "ddp_schedule_fill_bubbles: host allocation failed");
     }
 }
 
@@ -349,7 +370,7 @@ extern "C" int ddp_schedule_time_model(int L, int H, const int64_t *t_fp_ns, con
         }
         if (out_period_ns) *out_period_ns = (int64_t)period;
         return DDP_OK;
-    } catch (const std::exception &e) {
-        return ddp::fail(nullptr, DDP_ENOMEM, std::string("ddp_schedule_time_model: host allocation failed: ") + e.what());
+    } catch (...) {
+        return ddp::fail_nothrow(nullptr, DDP_ENOMEM, "ddp_schedule_time_model: host allocation failed");
     }
 }

@@ -13,7 +13,7 @@ import pytest
 import torch
 
 from paper_2502_11058_amd import workloads as W
-from test_gpu_parity import _bits, _need_gpu, _np, assert_bf16_within_one_ulp, assert_close_fp32, progress, run_trajectory
+from test_gpu_parity import Tally, _bits, _need_gpu, _np, assert_bf16_within_one_ulp, assert_close_fp32, progress, run_trajectory
 
 pytestmark = pytest.mark.gpu
 
@@ -294,3 +294,128 @@ def test_llama3_8b_ragged_schedule_sampled_trajectory(oracle):
     if free < need:
         pytest.skip(f"needs {need / 1e9:.0f} GB of free HBM, {free / 1e9:.0f} GB available")
     assert run_sampled(oracle, w, iters=8) == 1.0
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# every element of one full-size iteration against the oracle, streamed layer by layer
+# ----------------------------------------------------------------------------------------------------------------
+
+def run_all_elements(oracle, w, fused, warm=2, placement=None, stats_layer_cap=260_000_000):
+    """One iteration at full size in bench.py's launch configuration, EVERY element of its result against the oracle.
+
+    After `warm` iterations through the GPU path (so that the optimizer state is what a run holds, not zeros) the state
+    before iteration r = warm is copied to the host layer by layer, the GPU takes the step (four calls, or the fused entry
+    point) over the whole model in its usual launches, and then the oracle takes the same step one layer at a time on
+    the host copy - pack, rank-order mean with that layer's range of the peer buffers, statistics, unpack, optimizer -
+    and all of the layer's parameters, moments and bf16 model copy are compared with what the GPU holds, bit for bit.
+    The oracle never sees a value the GPU path computed in this iteration."""
+    from paper_2502_11058_amd.harness import DeviceReplica
+    _need_gpu()
+    oracle.set_threads(16)
+    gc.collect()
+    torch.cuda.empty_cache()
+    rep = DeviceReplica(w, 0, placement_probe=placement)
+    rep.init_params()
+    N, H, L = w.n_replicas, w.period, w.n_layers
+    hyper = dict(lr=w.lr, momentum=w.momentum, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay)
+
+    def stage(r):
+        """Inputs of iteration r: fresh gradients, peers = an independent gather of the slot's tensors + drift."""
+        S = rep.sets[r % H]
+        off, order_t, total = oracle.slot_offsets(rep.layer_of, rep.numel, S)
+        assert rep.ctx.ddp_slot_numel(r % H) == total
+        rep.fill_grads(r)
+        if total:
+            base = torch.cat([rep.sync[t] for t in order_t])
+            rep.fill_peers_from(base, r, total)
+            del base
+        return S, total
+
+    def gpu_step(r, rank):
+        if fused:
+            rep.fused_step(r, rank)
+        else:
+            rep.step(r, rank)
+
+    for r in range(warm):
+        stage(r)
+        gpu_step(r, r % N)
+    r = warm
+    rank = r % N
+    S, total = stage(r)
+    assert total > 0, "pick an iteration whose slot is not empty"
+    tid, toff, lid, lbeg = rep.ctx.ddp_slot_layout(r % H)
+    assert lid.tolist() == list(S)
+    torch.cuda.synchronize()
+
+    # element range of every layer in the arenas (tensors lie back to back in registration order)
+    first = [None] * L
+    last = [None] * L
+    for t, l in enumerate(rep.layer_of):
+        first[l] = t if first[l] is None else first[l]
+        last[l] = t
+    rng = [(int(rep.offsets[first[l]]), int(rep.offsets[last[l]]) + rep.numel[last[l]]) for l in range(L)]
+
+    before = {}
+    for l in range(L):
+        lo, hi = rng[l]
+        before[l] = tuple(_np(a[lo:hi]) for a in (rep.a_sync, rep.a_s0, rep.a_s1, rep.a_grad))
+    progress(f"[{w.name}] state before iteration {r} on the host ({sum(x.nbytes for b in before.values() for x in b) / 1e9:.0f} GB)")
+    rep.stats.fill_(-1.0)
+    gpu_step(r, rank)
+    torch.cuda.synchronize()
+    stats = _np(rep.stats)
+    tally = Tally()
+    n_model = 0
+    for l in range(L):
+        lo, hi = rng[l]
+        p0, m0, v0, g = before.pop(l)
+        ts = list(range(first[l], last[l] + 1))
+        cuts = np.cumsum([0] + [rep.numel[t] for t in ts])
+        split = lambda a: [a[cuts[j]:cuts[j + 1]] for j in range(len(ts))]
+        wk = oracle.Worker([0] * len(ts), split(p0), w.optimizer, hyper, False)
+        wk.s0, wk.s1 = split(m0), split(v0)                                   # the optimizer state the run holds
+        wk.model = [np.empty(rep.numel[t], dtype=np.uint16) for t in ts]      # written by unpack and by the update
+        if l in S:
+            i = list(S).index(l)
+            b, e = int(lbeg[i]), int(lbeg[i + 1])
+            assert e - b == hi - lo
+            peers = [_np(x[b:e]) for x in rep.peers]
+            mean_ref, st_ref = wk.sync([0], peers, rank)
+            if not fused:                                                      # the four-call path leaves the mean in the flat buffer
+                assert np.array_equal(_bits(_np(rep.flat[b:e])), _bits(mean_ref)), f"mean of layer {l}"
+            if e - b <= stats_layer_cap:
+                assert stats[2 * i] == pytest.approx(st_ref[0][0], rel=1e-10), f"gamma of layer {l}"
+                assert stats[2 * i + 1] == pytest.approx(st_ref[0][1], rel=1e-10), f"mean norm of layer {l}"
+            del peers, mean_ref
+        wk.local_update(split(g), r + 1)
+        for name, arena, ref, atol in (("param", rep.a_sync, wk.p, 1e-9), ("m", rep.a_s0, wk.s0, 1e-12), ("v", rep.a_s1, wk.s1, 1e-16)):
+            got = _np(arena[lo:hi])
+            ref = np.concatenate(ref)
+            assert_close_fp32(got, ref, f"{name} of layer {l}", atol)          # the north star's bar ...
+            tally.add(got, ref)                                                # ... and how many are the same bits
+        got = _np(rep.a_model[lo:hi])
+        ref = np.concatenate(wk.model)
+        assert_bf16_within_one_ulp(got, ref, f"model copy of layer {l}")
+        assert np.array_equal(got, ref), f"model copy of layer {l}"
+        n_model += got.size
+        del wk, p0, m0, v0, g, got, ref
+        if l % 8 == 0 or l == L - 1:
+            progress(f"[{w.name}] {'fused' if fused else 'four calls'} r={r}: layers 0..{l} compared, every element")
+    assert tally.n == 3 * w.n_params and n_model == w.n_params
+    progress(f"[{w.name}] {'fused' if fused else 'four calls'}: {tally.n + n_model} values compared with the oracle, "
+             f"{100.0 * tally.frac():.6f}% bit-identical")
+    rep.close()
+    return tally.frac()
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("fused", [False, True])
+def test_llama2_7b_every_element_of_one_iteration(oracle, fused):
+    # the slab placed the way bench.py places it for the four calls; iteration 2 synchronises slot 2 (four blocks)
+    assert run_all_elements(oracle, W.llama2_7b(), fused, warm=2, placement="search" if not fused else None) == 1.0
+
+
+@pytest.mark.timeout(900)
+def test_llama3_8b_every_element_of_one_iteration(oracle):
+    assert run_all_elements(oracle, W.llama3_8b(), fused=True, warm=2) == 1.0

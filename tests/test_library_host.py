@@ -98,6 +98,36 @@ def test_alg2_equals_oracle_alg2(oracle):
         assert c >= _sets("opt", L, H, bp, comm)[2]
 
 
+def _branching_instance(L):
+    """Backward 1 per layer, communication alternating 0 / huge: every second layer leaves both of Algorithm 2's
+    branches open, so its solution set grows like the Fibonacci numbers."""
+    return np.ones(L, dtype=np.int64), np.array([0 if i % 2 == 0 else 10 ** 6 for i in range(L)], dtype=np.int64)
+
+
+def test_alg2_on_a_branching_instance_equals_oracle(oracle):
+    bp, comm = _branching_instance(40)
+    sizes, cost, omega = oracle.sched_alg2(bp, comm, 20)
+    assert len(omega) == 6765                                            # F(20)
+    sets, _, c = _sets("alg2", 40, 20, bp, comm)
+    assert sets == oracle.sets_from_sizes(40, sizes) and c == cost
+    assert B.ddp_schedule_alg2_solutions(bp, comm, 20) == len(omega)
+
+
+def test_alg2_search_is_bounded():
+    # L = 128, H = 64 on the same pattern would visit ~1e13 solutions: the library gives up after a fixed number of
+    # steps with DDP_ESCHED and names the exact policy, which solves the instance at once
+    import time
+    bp, comm = _branching_instance(128)
+    t0 = time.perf_counter()
+    for call in (lambda: _sets("alg2", 128, 64, bp, comm), lambda: B.ddp_schedule_alg2_solutions(bp, comm, 64)):
+        with pytest.raises(B.DdpError) as e:
+            call()
+        assert e.value.code == 6 and "DDP_SCHED_OPT" in str(e.value)
+    assert time.perf_counter() - t0 < 30.0
+    sets, _, c = _sets("opt", 128, 64, bp, comm)
+    assert sorted(l for S in sets for l in S) == list(range(128)) and c > 0
+
+
 def test_counter_example_of_optimal_hiding():
     bp, comm = [1, 1, 8, 1, 2], [2, 5, 2, 1, 9]
     assert _sets("alg2", 5, 2, bp, comm)[0::2] == ([[4, 3, 2], [1, 0]], 33)

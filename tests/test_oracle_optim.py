@@ -135,3 +135,65 @@ def test_threads_do_not_change_results(oracle):
     oracle.set_threads(1)
     for a, b in zip(*outs):
         assert np.array_equal(a, b)
+
+
+def test_adamw_hand_worked_dyadic_values(oracle):
+    # Values chosen so that every intermediate is a dyadic rational that fp32 holds exactly: the result is fixed by the
+    # AdamW definition alone, bit for bit, whatever the operation order.  beta1 = 1/2, beta2 = 3/4, step 1:
+    #   m = g/2, v = g^2/4, 1/(1-beta1) = 2, 1/sqrt(1-beta2) = 2, so m/(sqrt(v)*2 + eps) = (g/2)/(|g| + eps)
+    # with lr = 1/2, eps = 0, weight_decay = 1/4: p' = p*(1 - 1/8) - (1/2*2) * sign(g)/2 = 7p/8 - sign(g)/2
+    g = np.array([1.0, -2.0, 0.25, -8.0, 3.0], dtype=np.float32)
+    p0 = np.array([1.0, 16.0, -4.0, 0.5, 8.0], dtype=np.float32)
+    p, m, v = p0.copy(), np.zeros_like(p0), np.zeros_like(p0)
+    oracle.adamw(p, g, m, v, None, 0.5, 0.5, 0.75, 0.0, 0.25, 1)
+    assert np.array_equal(m, g / 2) and np.array_equal(v, g * g / 4)
+    assert np.array_equal(p, np.array([0.375, 14.5, -4.0, 0.9375, 6.5], dtype=np.float32))
+    # eps = 1 with g = +-1: (1/2)/(1 + 1) = 1/4, so p' = 7p/8 - sign(g)/4 ... and a second step from hand-set moments:
+    # step 2 would need 1/(1 - 1/4) = 4/3, not dyadic; instead pin the moment recurrences alone (they do not use it)
+    g1 = np.array([1.0, -1.0], dtype=np.float32)
+    p, m, v = np.array([8.0, 8.0], dtype=np.float32), np.zeros(2, dtype=np.float32), np.zeros(2, dtype=np.float32)
+    oracle.adamw(p, g1, m, v, None, 0.5, 0.5, 0.75, 1.0, 0.25, 1)
+    assert np.array_equal(p, np.array([6.75, 7.25], dtype=np.float32))
+    oracle.adamw(p, 2 * g1, m, v, None, 0.5, 0.5, 0.75, 1.0, 0.25, 2)
+    assert np.array_equal(m, np.array([1.25, -1.25], dtype=np.float32))       # 1/2 * 1/2 + 1/2 * 2
+    assert np.array_equal(v, np.array([1.1875, 1.1875], dtype=np.float32))    # 3/4 * 1/4 + 1/4 * 4
+
+
+def test_adamw_against_the_textbook_division_form(oracle):
+    # The AdamW of the literature divides by the bias corrections: mhat = m/(1-b1^t), vhat = v/(1-b2^t),
+    # p' = p(1 - lr wd) - lr mhat/(sqrt(vhat) + eps).  Evaluated in fp64 from the same fp32 state each step, it must
+    # agree with the oracle's fp32 step to a few units in the last place of p: 12 roundings of at most 2^-24 relative
+    # each on terms no larger than |p| + lr.
+    lr, b1, b2, eps, wd, n = 3e-4, 0.9, 0.95, 1e-8, 0.1, 20000
+    p, m, v = _rand(n, 21, 0.02), np.zeros(n, dtype=np.float32), np.zeros(n, dtype=np.float32)
+    b1d, b2d, lrd, wdd, epsd = (float(np.float32(x)) for x in (b1, b2, lr, wd, eps))
+    for t in range(1, 9):
+        g = _rand(n, 300 + t, 1e-3)
+        p64, m64, v64, g64 = (x.astype(np.float64) for x in (p, m, v, g))
+        m_ref = b1d * m64 + (1 - b1d) * g64
+        v_ref = b2d * v64 + (1 - b2d) * g64 * g64
+        p_ref = p64 * (1 - lrd * wdd) - lrd * (m_ref / (1 - b1d ** t)) / (np.sqrt(v_ref / (1 - b2d ** t)) + epsd)
+        oracle.adamw(p, g, m, v, None, lr, b1, b2, eps, wd, t)
+        assert np.max(np.abs(m - m_ref) / (np.abs(b1d * m64) + np.abs((1 - b1d) * g64) + 1e-30)) < 3 * 2.0 ** -24   # the two terms may cancel
+        assert np.max(np.abs(v - v_ref) / np.maximum(np.abs(v_ref), 1e-30)) < 4 * 2.0 ** -24
+        assert np.max(np.abs(p - p_ref) / (np.abs(p_ref) + lrd)) < 4 * 2.0 ** -24
+
+
+def test_adamw_bitwise_against_an_array_evaluation(oracle):
+    # A second evaluation of the documented operation sequence, written with whole-array fp32 operations (numpy rounds
+    # every fp32 operation, sqrt and division included, correctly): the bits must be the same.  A dropped or fused
+    # operation, a changed association or a different constant in the loop of the oracle fails this.
+    f = np.float32
+    lr, b1, b2, eps, wd, n = f(3e-4), f(0.9), f(0.95), f(1e-8), f(0.1), 50000
+    p, m, v = _rand(n, 31, 0.02), np.zeros(n, dtype=np.float32), np.zeros(n, dtype=np.float32)
+    pr, mr, vr = p.copy(), m.copy(), v.copy()
+    for t in range(1, 6):
+        g = _rand(n, 400 + t, 1e-3)
+        oracle.adamw(p, g, m, v, None, float(lr), float(b1), float(b2), float(eps), float(wd), t)
+        step_size = lr * f(1.0 / (1.0 - float(b1) ** t))
+        rs2 = f(1.0 / np.sqrt(1.0 - float(b2) ** t))
+        mr = b1 * mr + (f(1) - b1) * g
+        vr = b2 * vr + ((f(1) - b2) * g) * g
+        pr = pr * (f(1) - lr * wd) - step_size * (mr / (np.sqrt(vr) * rs2 + eps))
+        for a, b in ((p, pr), (m, mr), (v, vr)):
+            assert a.dtype == b.dtype == np.float32 and np.array_equal(a.view(np.uint32), b.view(np.uint32))
