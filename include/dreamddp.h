@@ -62,7 +62,9 @@ enum { DDP_MAX_REPLICAS = 64 };
  *   OPT          exact minimiser of Eq. (8) over all cuts of the BP-ordered layer sequence into H consecutive,
  *                possibly empty sets; ties -> lexicographically largest (|L_1|, |L_2|, ...).
  *   ALG2         Algorithm 2: depth-first search pruned by Properties 1-3, argmin over its solution set
- *                (first minimum in visiting order, assign-branch visited first). */
+ *                (first minimum in visiting order, assign-branch visited first).  The solution set can grow
+ *                exponentially with min(L, H) (Sec. 3.3): the search gives up after 5e7 placement steps (well under
+ *                a second) with DDP_ESCHED; OPT solves the same objective exactly in O(L^2 H). */
 enum {
     DDP_SCHED_ENP = 0,
     DDP_SCHED_ROUND_ROBIN = 1,
@@ -82,7 +84,7 @@ enum {
  *   out_cost_ns     host, nullable: Eq. (8) of the result (only for contiguous policies ENP, FULL, OPT, ALG2;
  *                   -1 otherwise).
  * Errors: DDP_EINVAL for L < 1, H < 1, unknown policy, NULL outputs, negative times, or time sums that
- * would overflow int64. */
+ * would overflow int64; DDP_ESCHED when ALG2's search exceeds its step budget. */
 int ddp_schedule(int policy, int L, int H, const int64_t *t_fp_ns, const int64_t *t_bp_ns, const int64_t *t_comm_ns,
                  int32_t *out_slot, int32_t *out_set_ptr, int32_t *out_set_layers, int64_t *out_cost_ns);
 
@@ -91,7 +93,8 @@ int ddp_schedule(int policy, int L, int H, const int64_t *t_fp_ns, const int64_t
 int ddp_schedule_cost(int L, int H, const int64_t *t_bp_ns, const int64_t *t_comm_ns, const int32_t *set_ptr,
                       const int32_t *set_layers, int64_t *out_cost_ns);
 
-/* Size of Algorithm 2's solution set Omega for the instance (Sec. 3.3, complexity analysis).  Host pointers. */
+/* Size of Algorithm 2's solution set Omega for the instance (Sec. 3.3, complexity analysis).  Host pointers.
+ * DDP_ESCHED if the search exceeds its step budget (see DDP_SCHED_ALG2). */
 int ddp_schedule_alg2_solutions(int L, int H, const int64_t *t_bp_ns, const int64_t *t_comm_ns, int64_t *out_count);
 
 /* Sec. 3.4 "filling the bubble time", Eq. (12), Algorithm 2 lines 3-6.  Input: a schedule that is a cut of the
@@ -287,6 +290,32 @@ int ddp_fused_sync_update_layers(ddp_ctx *ctx, int slot, int layer_first, int la
 enum { DDP_STATIC_SCRATCH_BYTES = 16 << 20 };
 int ddp_partial_average_static(ddp_ctx *ctx, int slot, const float *flat_local, const float *const *peers, int N,
                                int local_rank, float *flat_out, double *layer_stats, void *stream);
+
+/* Streams for the overlap of Sec. 3.2 on one GPU.  The paper hides a layer's synchronisation under the backward pass of
+ * the layers below it; on a single GPU the synchronisation + update kernels and the backward kernels would compete for
+ * the same compute units (a matrix product that fills every CU leaves no slot for a second stream).  A stream made here
+ * runs its kernels only on compute units [cu_first, cu_first + cu_count) of the device's enumeration (the order of the
+ * bits of hipExtStreamCreateWithCUMask, which the driver spreads evenly over the chip's XCDs), at the default priority.
+ * The caller gives the backward pass a stream over one range and the layer-wise calls (ddp_fused_sync_update_layers, ...)
+ * a stream over the rest, and orders the two with events as with any two streams.  The handle is a hipStream_t; it is
+ * owned by the caller and released with ddp_stream_destroy once its work is complete.  `device` must be the current
+ * device.  Errors: DDP_EINVAL (range), DDP_ESTATE (device not current), DDP_EHIP. */
+int ddp_device_cu_count(int device, int *out_cus);
+int ddp_stream_create_cu_range(int device, int cu_first, int cu_count, void **out_stream);
+int ddp_stream_destroy(void *stream);
+
+/* Measurement aid, not a step of the method: one kernel in the launch shape of the library's streaming kernels (256-thread
+ * workgroups, chunk_bytes of every stream per workgroup, 128-bit buffer accesses with the streaming hint, two vectors per
+ * thread and stream in flight, lds_pad bytes of unused dynamic LDS per workgroup to cap residency) that only reads n_read
+ * streams and writes n_write streams of `bytes` bytes each (every written vector is 1 + the sum of the vectors read).
+ * Timed by the caller with events on `stream`, it shows what the memory system gives a kernel with that mix of
+ * streams: the practical ceiling beside the 8 TB/s peak that the roofline fractions are quoted against.
+ *   read_ptrs / write_ptrs  host arrays of n_read / n_write device pointers, 16-byte aligned, each >= bytes long, no overlap
+ *   n_read in {0, 1, 2, 3, 4, 8, 16}, n_write in [0, 4], not both 0; bytes a multiple of 16; chunk_bytes a multiple of 4096
+ *   in [4096, 4 MiB]; lds_pad in [0, 65536].  Uses the current device; needs no context.  Errors: DDP_EINVAL, DDP_EALIGN,
+ *   DDP_EHIP; message via ddp_last_error(NULL). */
+int ddp_stream_probe(int n_read, int n_write, int64_t bytes, const void *const *read_ptrs, void *const *write_ptrs,
+                     int chunk_bytes, int lds_pad, void *stream);
 
 /* Message of the last failure on this context (ctx == NULL: last failure of ddp_create / ddp_schedule* in
  * this thread).  Never NULL; valid until the next call on the same context / thread. */

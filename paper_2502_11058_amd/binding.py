@@ -28,7 +28,7 @@ EXPORTS = [
     "ddp_register_model", "ddp_set_schedule", "ddp_slot_numel", "ddp_slot_num_layers", "ddp_slot_num_tensors",
     "ddp_slot_layout", "ddp_pack", "ddp_partial_average", "ddp_unpack", "ddp_local_update", "ddp_fused_sync_update",
     "ddp_pack_wire16", "ddp_partial_average_wire16", "ddp_fused_sync_update_wire16",
-    "ddp_local_update_layers", "ddp_fused_sync_update_layers", "ddp_partial_average_static", "ddp_last_error",
+    "ddp_local_update_layers", "ddp_fused_sync_update_layers", "ddp_partial_average_static", "ddp_stream_probe", "ddp_device_cu_count", "ddp_stream_create_cu_range", "ddp_stream_destroy", "ddp_last_error",
 ]
 
 
@@ -80,6 +80,10 @@ def lib():
         l.ddp_local_update_layers.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(ddp_opt), C.c_void_p]
         l.ddp_fused_sync_update_layers.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
                                                    C.c_void_p, C.POINTER(ddp_opt), C.c_void_p]
+        l.ddp_device_cu_count.argtypes = [C.c_int, C.POINTER(C.c_int)]
+        l.ddp_stream_create_cu_range.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_void_p)]
+        l.ddp_stream_destroy.argtypes = [C.c_void_p]
+        l.ddp_stream_probe.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         l.ddp_schedule.argtypes = [C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 7
         l.ddp_schedule_cost.argtypes = [C.c_int, C.c_int] + [C.c_void_p] * 5
         l.ddp_schedule_alg2_solutions.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -209,6 +213,32 @@ def _peers_arg(peers):
     if not peers:
         return None
     return peers if isinstance(peers, C.Array) else _dev_ptrs(list(peers))
+
+
+def ddp_stream_probe(read_tensors, write_tensors, nbytes: int, chunk_bytes: int = 8192, lds_pad: int = 65536, stream=None) -> None:
+    """Enqueue the read/write reference kernel over the first nbytes of every given tensor (see the header)."""
+    rd = _dev_ptrs(list(read_tensors)) if read_tensors else None
+    wr = _dev_ptrs(list(write_tensors)) if write_tensors else None
+    _check(lib().ddp_stream_probe(len(read_tensors or []), len(write_tensors or []), int(nbytes), None if rd is None else C.addressof(rd),
+                                  None if wr is None else C.addressof(wr), chunk_bytes, lds_pad, _stream_handle(stream)))
+
+
+def ddp_device_cu_count(device: int = 0) -> int:
+    n = C.c_int(0)
+    _check(lib().ddp_device_cu_count(device, C.byref(n)))
+    return n.value
+
+
+def ddp_stream_create_cu_range(device: int, cu_first: int, cu_count: int) -> int:
+    """-> hipStream_t handle (an int) of a stream confined to those compute units; wrap it with
+    torch.cuda.ExternalStream(handle) to run torch work on it, release it with ddp_stream_destroy."""
+    h = C.c_void_p()
+    _check(lib().ddp_stream_create_cu_range(device, cu_first, cu_count, C.byref(h)))
+    return int(h.value)
+
+
+def ddp_stream_destroy(handle: int) -> None:
+    _check(lib().ddp_stream_destroy(C.c_void_p(handle)))
 
 
 class Context:

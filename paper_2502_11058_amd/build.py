@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(LIB_DIR, "libdreamddp.so")
-SOURCES = ["ddp_schedule.cpp", "ddp_context.hip", "ddp_noalloc.hip", "ddp_kernels_copy.hip", "ddp_kernels_mean.hip",
+SOURCES = ["ddp_schedule.cpp", "ddp_context.hip", "ddp_noalloc.hip", "ddp_probe.hip", "ddp_stream.hip", "ddp_kernels_copy.hip", "ddp_kernels_mean.hip",
            "ddp_kernels_update.hip", "ddp_kernels_fused.hip", "ddp_kernels_fused_dense.hip"]
 
 FLAGS = [

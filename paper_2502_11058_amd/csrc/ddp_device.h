@@ -363,6 +363,18 @@ __device__ __forceinline__ void fused_math4(const f32x4 (&pv)[NREP - 1], typenam
     x = m;
 }
 
+// Run-time replica counts (the kernels compiled for a fixed count keep all replicas in registers): a thread parks
+// each vector it loads in LDS while it forms the rank-order sum, and reads the vectors back for the statistics, so every
+// replica is fetched from memory once.  The staging area is dynamic LDS laid out [replica][thread] (each thread only
+// ever touches its own column: no barrier needed, no bank conflicts); with kStageBytes of it, stage_threads(N) threads
+// of the workgroup (whole wavefronts) take part in the vector loop.
+constexpr int kStageBytes = 65536;
+inline int stage_threads(int n_replicas) {
+    int t = kStageBytes / 16 / (n_replicas > 0 ? n_replicas : 1) / kWave * kWave;
+    return t > kThreads ? kThreads : t;  // at least one wavefront up to DDP_MAX_REPLICAS = 64
+}
+static_assert(kStageBytes / 16 / DDP_MAX_REPLICAS >= kWave, "the staging area must hold one wavefront at the largest replica count");
+
 // lds_pad: bytes of dynamic LDS requested per workgroup although no kernel uses them.  A CU has 160 KiB, so the pad
 // caps how many workgroups are resident per CU, i.e. how wide the window of addresses in flight is.
 template <class K, class... Args>

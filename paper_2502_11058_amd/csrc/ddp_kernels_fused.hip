@@ -16,6 +16,7 @@ struct FusedArgs {
     int n;
     int local_rank;
     int chunk_elems;
+    int stage_threads;  // run-time replica count with statistics: threads that take part in the vector loop
 };
 
 // Both cases of Eq. (5) in one pass.  For a chunk of a scheduled tensor the average over the N replicas is formed from
@@ -153,7 +154,12 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
                 store4(v, pl, av, bv);
             }
         } else {
-            for (int v = tid; v < nv; v += kThreads) {
+            // run-time replica count; with statistics the terms are parked in LDS (see stage_threads) so that the
+            // peers are fetched once, and only the first `vt` threads take part
+            extern __shared__ __align__(16) unsigned char dyn_lds[];
+            f32x4 *stage = reinterpret_cast<f32x4 *>(dyn_lds);
+            const int vt = STATS ? a.stage_threads : kThreads;
+            for (int v = tid; v < nv && tid < vt; v += vt) {
                 f32x4 pl = ld<NT>(p4 + v);
                 const gvec gv = ld<NT>(g4 + v);
                 f32x4 av = ld<NT>(a4 + v);
@@ -163,11 +169,15 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
                 f32x4 loc = pl;
                 if constexpr (W16) loc = bf16_widen4(bf16_rne4(pl));
                 auto term = [&](int k) -> f32x4 { return k == lr ? loc : wire4<W16, NT>(a.x[k], vfo + v); };
-                f32x4 acc = term(0);
-                for (int k = 1; k < nrep; ++k) acc = acc + term(k);
+                f32x4 acc{};
+                for (int k = 0; k < nrep; ++k) {
+                    const f32x4 x = term(k);
+                    if constexpr (STATS) stage[k * vt + tid] = x;
+                    acc = k == 0 ? x : acc + x;
+                }
                 f32x4 m = acc * inv_n;
                 if constexpr (STATS) {
-                    for (int k = 0; k < nrep; ++k) stats4(m, term(k));
+                    for (int k = 0; k < nrep; ++k) stats4(m, stage[k * vt + tid]);
                     msq4(m);
                 }
                 if constexpr (!UTS) step4(gv, m, av, bv);
@@ -191,8 +201,11 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
 template <bool A, bool G, bool M, int NR>
 static int launch_fused_n(const FusedLaunch &f, const FusedArgs &fa, void *stream) {
     const bool st = f.partials != nullptr;
+    // dynamic LDS: the residency pad, or the staging area of the run-time replica count if that is larger
+    const int need = NR == 0 && st ? f.n_replicas * stage_threads(f.n_replicas) * 16 : 0;
+    const int lds = f.lds_pad > need ? f.lds_pad : need;
 #define DDP_FUSED(W, U)                                                                                \
-    return st ? launch(fused_kernel<A, G, M, NR, true, W, U>, f.n_chunks, stream, f.lds_pad, fa)       \
+    return st ? launch(fused_kernel<A, G, M, NR, true, W, U>, f.n_chunks, stream, lds, fa)             \
               : launch(fused_kernel<A, G, M, NR, false, W, U>, f.n_chunks, stream, f.lds_pad, fa);
     if (f.wire16) {
         if (f.update_first) { DDP_FUSED(true, true) }
@@ -226,6 +239,7 @@ int launch_fused(const FusedLaunch &f, void *stream) {
     fa.n = f.n_replicas;
     fa.local_rank = f.local_rank;
     fa.chunk_elems = f.chunk_elems;
+    fa.stage_threads = stage_threads(f.n_replicas);
     const bool adam = f.kind == DDP_OPT_ADAMW, gb = f.grad_dtype == DDP_BF16, md = f.with_model;
     int rc = (int)hipErrorInvalidValue;
 #define DDP_F(A, G, M) \

@@ -11,6 +11,7 @@ struct MeanArgs {
     double *partials;
     float inv_n;
     int n;
+    int stage_threads;  // run-time replica count with statistics: threads that take part in the vector loop
 };
 
 // Eq. (5), second case.  NREP > 0: replica count known at compile time (pointer loads and the sum fully
@@ -106,16 +107,36 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
             }
             put4(v, m);
         }
+    } else if constexpr (STATS) {
+        extern __shared__ __align__(16) unsigned char dyn_lds[];
+        f32x4 *stage = reinterpret_cast<f32x4 *>(dyn_lds);
+        const int vt = a.stage_threads;
+        if (tid < vt) {
+            for (int v = tid; v < nv; v += vt) {
+                f32x4 acc{};
+                for (int k0 = 0; k0 < nrep; k0 += 4) {  // four loads in flight, then park and add them in rank order
+                    f32x4 x[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (k0 + j < nrep) x[j] = wire4<W16, NT>(a.x[k0 + j], vbase + v);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (k0 + j < nrep) {
+                            stage[(k0 + j) * vt + tid] = x[j];
+                            acc = k0 + j == 0 ? x[j] : acc + x[j];
+                        }
+                }
+                const f32x4 m = acc * inv_n;
+                for (int k = 0; k < nrep; ++k) stats4(m, stage[k * vt + tid]);
+                msq4(m);
+                st<NT>(o4 + v, m);
+            }
+        }
     } else {
         for (int v = tid; v < nv; v += kThreads) {
             f32x4 acc = wire4<W16, NT>(a.x[0], vbase + v);
             for (int k = 1; k < nrep; ++k) acc = acc + wire4<W16, NT>(a.x[k], vbase + v);
-            const f32x4 m = acc * inv_n;
-            if constexpr (STATS) {
-                for (int k = 0; k < nrep; ++k) stats4(m, wire4<W16, false>(a.x[k], vbase + v));
-                msq4(m);
-            }
-            st<NT>(o4 + v, m);
+            st<NT>(o4 + v, acc * inv_n);
         }
     }
 
@@ -186,15 +207,22 @@ __global__ __launch_bounds__(kThreads) void stats_single_kernel(const double *__
     }
 }
 
+// Dynamic LDS of a launch: the residency pad, or the staging area of the run-time replica count if that is larger.
+template <int NREP>
+int mean_lds(const MeanLaunch &a) {
+    const int need = NREP == 0 && a.partials ? a.n_replicas * stage_threads(a.n_replicas) * 16 : 0;
+    return a.lds_pad > need ? a.lds_pad : need;
+}
+
 template <int NREP>
 int launch_mean16_n(const MeanArgs &ma, const MeanLaunch &a, void *stream) {
-    if (a.partials) return launch(mean_kernel<NREP, true, true, true>, a.n_chunks, stream, a.lds_pad, ma);
+    if (a.partials) return launch(mean_kernel<NREP, true, true, true>, a.n_chunks, stream, mean_lds<NREP>(a), ma);
     return launch(mean_kernel<NREP, false, true, true>, a.n_chunks, stream, a.lds_pad, ma);
 }
 
 template <int NREP>
 int launch_mean_n(const MeanArgs &ma, const MeanLaunch &a, void *stream) {
-    if (a.partials) return a.nontemporal ? launch(mean_kernel<NREP, true, true>, a.n_chunks, stream, a.lds_pad, ma) : launch(mean_kernel<NREP, true, false>, a.n_chunks, stream, a.lds_pad, ma);
+    if (a.partials) return a.nontemporal ? launch(mean_kernel<NREP, true, true>, a.n_chunks, stream, mean_lds<NREP>(a), ma) : launch(mean_kernel<NREP, true, false>, a.n_chunks, stream, mean_lds<NREP>(a), ma);
     return a.nontemporal ? launch(mean_kernel<NREP, false, true>, a.n_chunks, stream, a.lds_pad, ma) : launch(mean_kernel<NREP, false, false>, a.n_chunks, stream, a.lds_pad, ma);
 }
 
@@ -225,6 +253,7 @@ int launch_mean(const MeanLaunch &a, void *stream) {
     ma.partials = a.partials;
     ma.inv_n = a.inv_n;
     ma.n = a.n_replicas;
+    ma.stage_threads = stage_threads(a.n_replicas);
     int rc;
     if (a.wire16) {
         switch (a.n_replicas) {

@@ -12,6 +12,8 @@ token embedding, position embedding and final-norm + LM head are layers of their
 from __future__ import annotations
 
 import hashlib
+import json
+import os
 from dataclasses import dataclass, field
 from typing import Dict, List, Tuple
 
@@ -68,21 +70,35 @@ class Workload:
 # shapes
 # ----------------------------------------------------------------------------------------------------------
 
-def tiny() -> Workload:
-    """8-layer MLP, each layer a 256x256 weight and a bias of 256; N=4, H=4, SGD-momentum."""
+CONFIG_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "configs")
+
+
+def load_config(name: str) -> Dict[str, object]:
+    """The benchmark configurations are data: configs/<name>.json holds the model dimensions, N, H, the optimizer and
+    its hyper-parameters, the value distributions and the default schedule policy."""
+    with open(os.path.join(CONFIG_DIR, name + ".json")) as f:
+        return json.load(f)
+
+
+def _common(c: Dict[str, object]) -> Dict[str, object]:
+    keys = ("n_replicas", "period", "optimizer", "param_dtype", "lr", "momentum", "beta1", "beta2", "eps", "weight_decay",
+            "sigma_param", "sigma_drift", "sigma_grad", "iterations", "policy", "time_noise")
+    return {k: c[k] for k in keys if k in c}
+
+
+def _mlp_tensors(c) -> List[TensorSpec]:
     ts: List[TensorSpec] = []
-    for l in range(8):
-        ts.append(TensorSpec(f"mlp.{l}.weight", l, 256 * 256))
-        ts.append(TensorSpec(f"mlp.{l}.bias", l, 256))
-    return Workload("tiny", ts, n_replicas=4, period=4, optimizer="sgdm", param_dtype="f32", lr=0.01,
-                    sigma_drift=1e-3, sigma_grad=1e-2, iterations=16, policy="enp")
+    n = int(c["width"])
+    for l in range(int(c["n_layers"])):
+        ts.append(TensorSpec(f"mlp.{l}.weight", l, n * n))
+        ts.append(TensorSpec(f"mlp.{l}.bias", l, n))
+    return ts
 
 
-def gpt2_small(with_biases: bool = False) -> Workload:
-    """12 blocks at d=768 plus token and position embeddings; fp32, N=8, H=4, SGD-momentum."""
-    d, ff, vocab, ctx = 768, 3072, 50257, 1024
+def _gpt2_tensors(c, with_biases: bool) -> List[TensorSpec]:
+    d, ff, vocab, ctx, nb = (int(c[k]) for k in ("d", "ffn", "vocab", "context", "n_blocks"))
     ts = [TensorSpec("wte", 0, vocab * d), TensorSpec("wpe", 1, ctx * d)]
-    for b in range(12):
+    for b in range(nb):
         l = 2 + b
         ts.append(TensorSpec(f"h.{b}.ln_1.weight", l, d))
         ts.append(TensorSpec(f"h.{b}.ln_1.bias", l, d))
@@ -101,18 +117,16 @@ def gpt2_small(with_biases: bool = False) -> Workload:
         if with_biases:
             ts.append(TensorSpec(f"h.{b}.mlp.c_proj.bias", l, d))
     if with_biases:
-        ts.append(TensorSpec("ln_f.weight", 14, d))
-        ts.append(TensorSpec("ln_f.bias", 14, d))
-    return Workload("gpt2_small", ts, n_replicas=8, period=4, optimizer="sgdm", param_dtype="f32", lr=0.01,
-                    sigma_drift=1e-3, sigma_grad=1e-2, iterations=16, policy="opt")
+        ts.append(TensorSpec("ln_f.weight", 2 + nb, d))
+        ts.append(TensorSpec("ln_f.bias", 2 + nb, d))
+    return ts
 
 
-def _llama(name: str, n_blocks: int, d: int, ffn: int, n_heads: int, n_kv: int, vocab: int, *, n_replicas: int,
-           period: int, iterations: int, policy: str, time_noise: bool) -> Workload:
-    hd = d // n_heads
-    kv = n_kv * hd
+def _llama_tensors(c) -> List[TensorSpec]:
+    nb, d, ffn, nh, nkv, vocab = (int(c[k]) for k in ("n_blocks", "d", "ffn", "n_heads", "n_kv", "vocab"))
+    kv = nkv * (d // nh)
     ts = [TensorSpec("embed_tokens", 0, vocab * d)]
-    for b in range(n_blocks):
+    for b in range(nb):
         l = 1 + b
         ts += [
             TensorSpec(f"layers.{b}.input_layernorm", l, d),
@@ -125,25 +139,52 @@ def _llama(name: str, n_blocks: int, d: int, ffn: int, n_heads: int, n_kv: int, 
             TensorSpec(f"layers.{b}.up_proj", l, d * ffn),
             TensorSpec(f"layers.{b}.down_proj", l, ffn * d),
         ]
-    ts += [TensorSpec("norm", 1 + n_blocks, d), TensorSpec("lm_head", 1 + n_blocks, vocab * d)]
-    return Workload(name, ts, n_replicas=n_replicas, period=period, optimizer="adamw", param_dtype="bf16",
-                    lr=3e-4, sigma_drift=1e-4, sigma_grad=1e-3, iterations=iterations, policy=policy,
-                    time_noise=time_noise)
+    ts += [TensorSpec("norm", 1 + nb, d), TensorSpec("lm_head", 1 + nb, vocab * d)]
+    return ts
+
+
+def from_config(name: str, cfg: Dict[str, object] = None, **variant) -> Workload:
+    c = dict(cfg if cfg is not None else load_config(name))
+    fam = c["family"]
+    if fam == "mlp":
+        ts = _mlp_tensors(c)
+    elif fam == "gpt2":
+        ts = _gpt2_tensors(c, bool(variant.get("with_biases", False)))
+    elif fam == "llama":
+        ts = _llama_tensors(c)
+    else:
+        raise ValueError(f"unknown model family {fam!r} in configuration {name}")
+    return Workload(name, ts, **_common(c))
+
+
+def tiny() -> Workload:
+    """8-layer MLP, each layer a 256x256 weight and a bias of 256; N=4, H=4, SGD-momentum."""
+    return from_config("tiny")
+
+
+def gpt2_small(with_biases: bool = False) -> Workload:
+    """12 blocks at d=768 plus token and position embeddings; fp32, N=8, H=4, SGD-momentum."""
+    return from_config("gpt2_small", with_biases=with_biases)
+
+
+def _llama(name: str, n_blocks: int, d: int, ffn: int, n_heads: int, n_kv: int, vocab: int, *, n_replicas: int,
+           period: int, iterations: int, policy: str, time_noise: bool) -> Workload:
+    """A Llama-shaped workload from explicit dimensions (the hyper-parameters and distributions of the Llama configurations)."""
+    cfg = dict(load_config("llama2_7b"), n_blocks=n_blocks, d=d, ffn=ffn, n_heads=n_heads, n_kv=n_kv, vocab=vocab,
+               n_replicas=n_replicas, period=period, iterations=iterations, policy=policy, time_noise=time_noise)
+    return from_config(name, cfg)
 
 
 def tinyllama_1b() -> Workload:
-    return _llama("tinyllama_1b", 22, 2048, 5632, 32, 4, 32000, n_replicas=8, period=4, iterations=16,
-                  policy="enp", time_noise=False)
+    return from_config("tinyllama_1b")
 
 
 def llama2_7b() -> Workload:
-    return _llama("llama2_7b", 32, 4096, 11008, 32, 32, 32000, n_replicas=8, period=8, iterations=8,
-                  policy="enp", time_noise=False)
+    return from_config("llama2_7b")
 
 
 def llama3_8b() -> Workload:
-    return _llama("llama3_8b", 32, 4096, 14336, 32, 8, 128256, n_replicas=16, period=8, iterations=8,
-                  policy="opt", time_noise=True)
+    return from_config("llama3_8b")
 
 
 def odd(optimizer: str = "adamw", param_dtype: str = "bf16", n_replicas: int = 3, period: int = 2) -> Workload:
