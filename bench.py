@@ -210,6 +210,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="llama2_7b")
     ap.add_argument("--policy", default=None)
+    ap.add_argument("--replicas", type=int, default=None, metavar="N",
+                    help="override the workload's replica count (e.g. 17 to measure the kernels for run-time replica counts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stats", action="store_true", help="skip the per-layer statistics in the average")
     ap.add_argument("--option", action="append", default=[], help="library option name=value (repeatable)")
@@ -259,6 +261,8 @@ def main() -> int:
     if args.reference_rates:
         print(json.dumps(reference_rates(args.reference_gib)))
         return 0
+    if args.replicas is not None:
+        w.n_replicas = args.replicas
     if args.placement_study:
         import gc
         res = []

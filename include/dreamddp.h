@@ -131,11 +131,14 @@ int ddp_destroy(ddp_ctx *ctx);
  *                                               defaults 2048 / 2048 / 2048)
  *   "dispatch_ways"                             1..4096 (default 1): launch order of the workgroups; w > 1 cuts every
  *                                               chunk table into w contiguous segments and visits them round-robin
- *   "update_lds", "mean_lds", "copy_lds"        0..65536 bytes of dynamic LDS requested per workgroup without being
- *                                               used: caps the workgroups resident per CU (160 KiB of LDS each), which
- *                                               keeps the window of DRAM rows in flight narrow (defaults 65536 / 65536 /
- *                                               24576 = 2 / 2 / 6 workgroups per CU; the bf16-wire average uses half
- *                                               of mean_lds)
+ *   "update_wg_per_cu", "mean_wg_per_cu",       0..32 (defaults 2 / 2 / 6; 0 = no cap): most workgroups of that kernel family resident per
+ *   "copy_wg_per_cu"                            CU.  Few resident workgroups keep the window of DRAM rows in flight narrow, which
+ *                                               measures faster than full occupancy for these streaming kernels.  Enforced by
+ *                                               requesting (not using) dynamic LDS: LDS-per-CU / k bytes per workgroup, from the
+ *                                               sizes the device reports, so the cap holds on parts with another LDS size; a
+ *                                               kernel that needs LDS of its own gets the larger of the two.  The bf16-wire
+ *                                               average runs at twice mean_wg_per_cu (half the bytes per workgroup in flight)
+ *   "update_lds", "mean_lds", "copy_lds"        0..65536: the same cap given directly as bytes of LDS per workgroup (for sweeps)
  *   "nontemporal"                               0/1 (default 1): streaming cache hints on loads and stores
  *   "dense_path"                                0/1 (default 1): when the registered tensors lie back to back in every
  *                                               stream (one arena per stream, starts 16-byte aligned, bf16 streams

@@ -114,6 +114,18 @@ static void interleave_segments(std::vector<T> &v, int ways) {
     v.swap(out);
 }
 
+// Bytes of dynamic LDS a workgroup has to request (without using them) so that at most `wg_per_cu` workgroups of a
+// kernel with a few hundred bytes of static LDS are resident on a CU; 0 = no cap.  A request cannot exceed the
+// per-workgroup limit, so the smallest residency that can be enforced is ceil(LDS per CU / that limit).
+static int residency_pad(const ddp_ctx *c, int wg_per_cu) {
+    if (wg_per_cu <= 0) return 0;
+    int pad = c->lds_per_cu / wg_per_cu - 1024;      // room for the kernels' own static LDS and allocation granularity
+    pad = pad / 512 * 512;
+    const int cap = (c->lds_per_wg_max < 65536 ? c->lds_per_wg_max : 65536) - 1024;  // requests beyond 64 KiB are never made
+    if (pad > cap) pad = cap / 512 * 512;
+    return pad > 0 ? pad : 0;
+}
+
 static bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 }  // namespace ddp
@@ -134,6 +146,17 @@ extern "C" int ddp_create(ddp_ctx **out, int device) {
     ddp_ctx *c = new (std::nothrow) ddp_ctx();
     if (!c) return fail(nullptr, DDP_ENOMEM, "ddp_create: out of host memory");
     c->device = device;
+    // Residency caps are stated in workgroups per CU and turned into an LDS request from what this device reports, so
+    // that a part with another LDS size keeps the same residency.
+    int lds_cu = 0, lds_wg = 0;
+    if (hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, device) == hipSuccess && lds_cu > 0 &&
+        hipDeviceGetAttribute(&lds_wg, hipDeviceAttributeMaxSharedMemoryPerBlock, device) == hipSuccess && lds_wg > 0) {
+        c->lds_per_cu = lds_cu;
+        c->lds_per_wg_max = lds_wg;
+    }
+    c->update_lds = residency_pad(c, 2);
+    c->mean_lds = residency_pad(c, 2);
+    c->copy_lds = residency_pad(c, 6);
     // the device address of the library's fixed scratch array, resolved here once per device (the device is current)
     int rc = static_scratch_for(nullptr, device, &c->static_scratch);
     if (rc != DDP_OK) {
@@ -166,6 +189,11 @@ extern "C" int ddp_set_option(ddp_ctx *ctx, const char *name, int64_t value) {
             if (value < 1 || value > 4096) return fail(ctx, DDP_EINVAL, "ddp_set_option: dispatch_ways must be in [1, 4096]");
             if (ctx->registered) return fail(ctx, DDP_ESTATE, "ddp_set_option: dispatch_ways must be set before ddp_register_model");
             ctx->dispatch_ways = (int)value;
+            return DDP_OK;
+        }
+        if (k == "update_wg_per_cu" || k == "mean_wg_per_cu" || k == "copy_wg_per_cu") {
+            if (value < 0 || value > 32) return fail(ctx, DDP_EINVAL, "ddp_set_option: workgroups per CU must be in [0, 32] (0 = no cap)");
+            (k == "update_wg_per_cu" ? ctx->update_lds : k == "mean_wg_per_cu" ? ctx->mean_lds : ctx->copy_lds) = residency_pad(ctx, (int)value);
             return DDP_OK;
         }
         if (k == "update_lds" || k == "mean_lds" || k == "copy_lds") {

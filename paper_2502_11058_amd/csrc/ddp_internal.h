@@ -201,7 +201,8 @@ struct ddp_ctx {
     int64_t update_chunk = 2048, mean_chunk = 2048, copy_chunk = 2048;
     bool nontemporal = true;
     int dispatch_ways = 1;
-    int update_lds = 65536, mean_lds = 65536, copy_lds = 24576;  // dynamic-LDS pad per workgroup: caps residency per CU
+    int lds_per_cu = 163840, lds_per_wg_max = 65536;  // what the device reports (ddp_create); gfx950 values until then
+    int update_lds = 64512, mean_lds = 64512, copy_lds = 26112;  // dynamic-LDS pad per workgroup: caps residency per CU (2 / 2 / 6)
     // model
     bool registered = false;
     int L = 0, T = 0;

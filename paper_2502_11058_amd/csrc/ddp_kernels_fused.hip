@@ -219,6 +219,7 @@ static int launch_fused_n(const FusedLaunch &f, const FusedArgs &fa, void *strea
 template <bool A, bool G, bool M>
 static int launch_fused_t(const FusedLaunch &f, const FusedArgs &fa, void *stream) {
     switch (f.n_replicas) {
+        case 2: return launch_fused_n<A, G, M, 2>(f, fa, stream);
         case 4: return launch_fused_n<A, G, M, 4>(f, fa, stream);
         case 8: return launch_fused_n<A, G, M, 8>(f, fa, stream);
         case 16: return launch_fused_n<A, G, M, 16>(f, fa, stream);

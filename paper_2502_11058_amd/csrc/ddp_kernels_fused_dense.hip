@@ -91,7 +91,7 @@ static int launch_fused_dense_n(const FusedDenseLaunch &f, const FusedDenseArgs 
 #undef DDP_FUSED
 }
 
-bool fused_dense_supports(int n_replicas) { return n_replicas == 4 || n_replicas == 8 || n_replicas == 16; }
+bool fused_dense_supports(int n_replicas) { return n_replicas == 2 || n_replicas == 4 || n_replicas == 8 || n_replicas == 16; }
 
 int launch_fused_dense(const FusedDenseLaunch &f, void *stream) {
     if (f.d.n <= 0) return 0;
@@ -114,6 +114,7 @@ int launch_fused_dense(const FusedDenseLaunch &f, void *stream) {
     const bool adam = f.kind == DDP_OPT_ADAMW, gb = f.grad_dtype == DDP_BF16, md = f.with_model;
 #define DDP_F(A, G, M)                                                                                  \
     if (adam == A && gb == G && md == M) switch (f.n_replicas) {                                        \
+            case 2: return launch_fused_dense_n<A, G, M, 2>(f, fa, grid, stream);                       \
             case 4: return launch_fused_dense_n<A, G, M, 4>(f, fa, grid, stream);                       \
             case 8: return launch_fused_dense_n<A, G, M, 8>(f, fa, grid, stream);                       \
             case 16: return launch_fused_dense_n<A, G, M, 16>(f, fa, grid, stream);                     \

@@ -29,9 +29,24 @@ class BackwardOverlap:
     below, must not be driven this way.
     """
 
-    def __init__(self, rep: DeviceReplica, side_stream: Optional[torch.cuda.Stream] = None):
+    def __init__(self, rep: DeviceReplica, side_stream: Optional[torch.cuda.Stream] = None, side_cus: int = 0):
+        """side_cus > 0: divide the chip.  The side stream is confined to that many compute units and `main_stream`
+        to the others (ddp_stream_create_cu_range); the caller runs forward and backward under
+        `torch.cuda.stream(ov.main_stream)`.  A backward kernel that fills every CU otherwise leaves the side stream no
+        slot until it ends, and nothing is hidden.  Default: an ordinary side stream, `main_stream` = the current one."""
         self.rep = rep
-        self.side = side_stream or torch.cuda.Stream(device=rep.dev)
+        self._owned = []
+        if side_cus > 0 and side_stream is None:
+            ncu = B.ddp_device_cu_count(rep.dev.index)
+            if not 0 < side_cus < ncu:
+                raise ValueError(f"side_cus must be in (0, {ncu})")
+            self._owned = [B.ddp_stream_create_cu_range(rep.dev.index, 0, side_cus),
+                           B.ddp_stream_create_cu_range(rep.dev.index, side_cus, ncu - side_cus)]
+            self.side = torch.cuda.ExternalStream(self._owned[0], device=rep.dev)
+            self.main_stream = torch.cuda.ExternalStream(self._owned[1], device=rep.dev)
+        else:
+            self.side = side_stream or torch.cuda.Stream(device=rep.dev)
+            self.main_stream = torch.cuda.current_stream(rep.dev)
         self.params: List[torch.nn.Parameter] = []
         self._tensors_in_layer = [0] * rep.w.n_layers
         for i, l in enumerate(rep.layer_of):
@@ -47,6 +62,14 @@ class BackwardOverlap:
         self._left: Optional[List[int]] = None
         self._launched: List[bool] = []
         self.launch_order: List[int] = []       # layers in the order their calls were enqueued (last iteration)
+
+    def close(self) -> None:
+        """Release the CU-range streams made here (after their work is complete)."""
+        if self._owned:
+            torch.cuda.synchronize(self.rep.dev)
+            for h in self._owned:
+                B.ddp_stream_destroy(h)
+            self._owned = []
 
     def begin(self, r: int, local_rank: int = 0, with_stats: bool = True, wire16: bool = False,
               order: int = B.DDP_SYNC_THEN_UPDATE) -> None:

@@ -70,12 +70,35 @@ def counter_means(path: str, counter: str):
     return per, CAL_BYTES / cal[len(cal) // 2]
 
 
+def counters_table(path: str, min_dispatches: int = 1) -> None:
+    """Any --pmc run: mean of every counter per (kernel, grid size), for the library's kernels."""
+    db = _db(path)
+    per = collections.defaultdict(lambda: collections.defaultdict(list))
+    names = []
+    for name, cname, val, grid, wg in db.execute("select kernel_name, counter_name, value, grid_size, workgroup_size from counters_collection"):
+        if "ddp::" not in name:
+            continue
+        per[(name, grid // max(wg, 1))][cname].append(val)
+        if cname not in names:
+            names.append(cname)
+    print(f"{'kernel':72s} {'workgroups':>10s} {'n':>4s} " + " ".join(f"{c[:26]:>26s}" for c in names))
+    for key, cs in sorted(per.items(), key=lambda kv: -kv[0][1]):
+        n = len(next(iter(cs.values())))
+        if n < min_dispatches:
+            continue
+        print(f"{short(key[0])[:72]:72s} {key[1]:10d} {n:4d} " + " ".join(f"{sum(cs[c]) / max(len(cs[c]), 1):26.1f}" for c in names))
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("out", help="folder holding trace/, fetch/ and write/ of the three rocprofv3 runs")
+    ap.add_argument("out", help="folder holding trace/, fetch/ and write/ of the three rocprofv3 runs (or, with --counters, of one --pmc run)")
     ap.add_argument("--workload", default="llama2_7b")
     ap.add_argument("--traffic-json", default=None, help="update this file with the measured bytes per launch")
+    ap.add_argument("--counters", action="store_true", help="`out` is the folder of a single rocprofv3 --pmc run: print the mean of every counter per kernel")
     a = ap.parse_args()
+    if a.counters:
+        counters_table(a.out)
+        return 0
 
     print("== rocprofv3 --kernel-trace --stats: per-kernel durations (us)")
     print(f"{'kernel':100s} {'calls':>6s} {'total_us':>12s} {'avg_us':>11s} {'pct':>6s}")

@@ -300,17 +300,47 @@ def test_llama3_8b_ragged_schedule_sampled_trajectory(oracle):
 # every element of one full-size iteration against the oracle, streamed layer by layer
 # ----------------------------------------------------------------------------------------------------------------
 
-def _to_host(t: torch.Tensor) -> np.ndarray:
-    """Device tensor -> numpy through a pinned host buffer (several times faster than a pageable copy at these sizes; the
-    caching host allocator hands freed buffers out again, so the pinning cost is paid once per size)."""
-    v = t.view(torch.int16) if t.dtype == torch.bfloat16 else t
-    try:
-        buf = torch.empty(v.shape, dtype=v.dtype, pin_memory=True)
-    except RuntimeError:
-        buf = torch.empty(v.shape, dtype=v.dtype)
-    buf.copy_(v)
-    a = buf.numpy()
-    return a.view(np.uint16) if t.dtype == torch.bfloat16 else a
+class _Stager:
+    """Device -> host copies through two small pinned buffers, double-buffered: the copy of one piece runs while the
+    previous piece is moved into ordinary (pageable) host memory.  Only 512 MiB are ever pinned, and they are released
+    at the end: pinning the whole host copy (100 GB and more, which torch's host allocator then keeps cached for the
+    life of the process) leaves the GPU runtime without pinnable memory for its own queues and signals."""
+    PIECE = 256 << 20
+
+    def __init__(self):
+        try:
+            self.bufs = [torch.empty(self.PIECE, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+        except RuntimeError:
+            self.bufs = [torch.empty(self.PIECE, dtype=torch.uint8) for _ in range(2)]
+        self.done = [torch.cuda.Event(), torch.cuda.Event()]
+
+    def fetch(self, t: torch.Tensor) -> np.ndarray:
+        src = t.contiguous().view(torch.uint8)
+        n = src.numel()
+        out = np.empty(n, dtype=np.uint8)
+        pieces = [(o, min(self.PIECE, n - o)) for o in range(0, n, self.PIECE)]
+
+        def take(k):
+            o, l = pieces[k]
+            self.done[k % 2].synchronize()
+            out[o:o + l] = self.bufs[k % 2][:l].numpy()
+
+        for k, (o, l) in enumerate(pieces):
+            self.bufs[k % 2][:l].copy_(src[o:o + l], non_blocking=True)      # its previous content was taken in round k - 1
+            self.done[k % 2].record()
+            if k >= 1:
+                take(k - 1)
+        if pieces:
+            take(len(pieces) - 1)
+        dt = {torch.float32: np.float32, torch.bfloat16: np.uint16, torch.float64: np.float64}[t.dtype]
+        return out.view(dt)
+
+    def release(self):
+        torch.cuda.synchronize()
+        self.bufs = []
+        gc.collect()
+        if hasattr(torch._C, "_host_emptyCache"):
+            torch._C._host_emptyCache()
 
 
 def run_all_elements(oracle, w, warm=2, placement=None, stats_layer_cap=260_000_000, both_paths=True):
@@ -335,6 +365,8 @@ def run_all_elements(oracle, w, warm=2, placement=None, stats_layer_cap=260_000_
     gc.collect()
     torch.cuda.empty_cache()
     clock = {"host copy": 0.0, "oracle": 0.0, "compare": 0.0}
+    stager = _Stager()
+    _to_host = stager.fetch
     t_start = time.perf_counter()
     A = DeviceReplica(w, 0, placement_probe=placement)
     A.init_params()
@@ -471,6 +503,7 @@ def run_all_elements(oracle, w, warm=2, placement=None, stats_layer_cap=260_000_
     assert n_total == 3 * w.n_params and n_model == w.n_params
     progress(f"[{w.name}] {'fused' if fused_only else 'four calls' + (' and fused' if Bf is not None else '')}: "
              f"{n_total + n_model} values compared with the oracle, {100.0 * n_exact / n_total:.6f}% bit-identical")
+    stager.release()
     A.close()
     if Bf is not None:
         Bf.close()

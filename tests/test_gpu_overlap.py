@@ -42,15 +42,17 @@ def _np(t):
     return t.cpu().numpy()
 
 
-@pytest.mark.parametrize("wire16,order,policy", [(False, 0, "enp"), (True, 0, "round_robin"), (False, 1, "enp+fill")])
-def test_autograd_hooks_drive_the_layerwise_calls(oracle, wire16, order, policy):
+@pytest.mark.parametrize("wire16,order,policy,side_cus", [(False, 0, "enp", 0), (True, 0, "round_robin", 0), (False, 1, "enp+fill", 0),
+                                                          (False, 0, "enp", 32), (True, 1, "enp+fill", 64)])
+def test_autograd_hooks_drive_the_layerwise_calls(oracle, wire16, order, policy, side_cus):
+    # side_cus > 0: the chip is divided, the side stream on that many compute units, forward and backward on the others
     from paper_2502_11058_amd.harness import DeviceReplica
     from paper_2502_11058_amd.overlap import BackwardOverlap
     assert torch.cuda.is_available(), "no GPU visible: the HIP path cannot run (there is no CPU fallback)"
     w = _workload(4, 3, policy)
     rep = DeviceReplica(w, 0, wire16=wire16)
     rep.init_params()
-    ov = BackwardOverlap(rep)
+    ov = BackwardOverlap(rep, side_cus=side_cus)
     hyper = dict(lr=w.lr, momentum=w.momentum, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay)
     wk = oracle.Worker(rep.layer_of, [_np(t) for t in rep.sync], w.optimizer, hyper, True)
     gen = torch.Generator(device=rep.dev)
@@ -70,10 +72,12 @@ def test_autograd_hooks_drive_the_layerwise_calls(oracle, wire16, order, policy)
         tokens = torch.randint(0, VOCAB, (T,), device=rep.dev, generator=gen)
         targets = torch.randint(0, VOCAB, (T,), device=rep.dev, generator=gen)
         rep.stats.fill_(-1.0)
-        ov.begin(r, local_rank=rank, wire16=wire16, order=order)
-        loss = _loss(ov.params, tokens, targets)
-        loss.backward()
-        ov.end()
+        torch.cuda.synchronize()            # the inputs above were produced on the default stream
+        with torch.cuda.stream(ov.main_stream):
+            ov.begin(r, local_rank=rank, wire16=wire16, order=order)
+            loss = _loss(ov.params, tokens, targets)
+            loss.backward()
+            ov.end()
         torch.cuda.synchronize()
         losses.append(float(loss.detach()))
         # back-propagation finishes the output side first, and every layer got exactly one call
@@ -95,4 +99,5 @@ def test_autograd_hooks_drive_the_layerwise_calls(oracle, wire16, order, policy)
             assert np.array_equal(_np(rep.s1[t]).view(np.uint32), wk.s1[t].view(np.uint32)), f"v r={r} t={t}"
             assert np.array_equal(_np(rep.model[t]), wk.model[t]), f"model copy r={r} t={t}"
     assert all(np.isfinite(losses))
+    ov.close()
     rep.close()
