@@ -228,10 +228,13 @@ def main() -> int:
                     help="edge of the square bf16 products of --overlap (4096: one product fills the 256 CUs)")
     ap.add_argument("--front-pad-gib", type=int, default=None, metavar="G",
                     help="leave G GiB unused at the start of the worker's slab (default 0)")
+    ap.add_argument("--placement-search", default="search", choices=["search", "hole"],
+                    help="how the second measurement picks its slab: 'search' leaves 0/16/24/32/40 GiB unused in front of the data "
+                         "inside the allocation, 'hole' allocates and frees a placeholder of that size before the slab (nothing stays unused)")
     ap.add_argument("--no-placement-search", action="store_true",
-                    help="skip the second measurement (models of a billion parameters or more): the same K steps on a slab whose "
-                         "physical placement the harness picked by trying a few unused front pads; reported in an extra "
-                         "\"placement_search\" object, never in value")
+                    help="measure on the plain first allocation only.  Default for models of a billion parameters or more: measure that "
+                         "first (reported as no_placement_search / value_no_placement_search), then re-allocate the slab by the "
+                         "harness's placement search and measure value there")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 4 plain copies of 1 GiB (ddp_stream_probe, one read and one write stream) before the timed "
                          "region, as the known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
@@ -278,11 +281,6 @@ def main() -> int:
             torch.cuda.empty_cache()
         print(json.dumps({"placement_study_update_GBps": res, "workload": w.name, "front_pad_GiB": args.front_pad_gib or 0}))
         return 0
-    # The timed replica is allocated the plain way: one slab, first allocation, nothing left unused, no probing of the
-    # physical placement.  (--placement-search adds a second measurement on a slab picked by the harness's search.)
-    rep = DeviceReplica(w, 0, options=options, policy=args.policy, wire16=args.wire16, placement_probe=False,
-                        front_pad=(args.front_pad_gib or 0) << 30)
-
     def stage_inputs(rep):
         rep.init_params()
         rep.fill_grads(0)
@@ -295,7 +293,67 @@ def main() -> int:
             rep.fill_peers_from(rep.flat, 0, rep.flat.numel())
         torch.cuda.synchronize()
 
+    with_stats = not args.no_stats
+
+    def plain_measurement(rep):
+        """W warm-up and K timed steps of the four calls, then of the fused entry point, on the wall clock; the update
+        kernel's own rate from events around its K launches."""
+        Hn = len(rep.sets)
+        for r in range(args.warmup):
+            rep.step(r, with_stats=with_stats)
+        torch.cuda.synchronize()
+        stream = torch.cuda.current_stream()
+        evs = []
+        t0 = time.perf_counter()
+        for r in range(args.warmup, args.warmup + args.steps):
+            slot = r % Hn
+            c = rep.ctx
+            c.ddp_pack(slot, rep.flat)
+            c.ddp_partial_average(slot, rep.flat, rep._peers_arr, len(rep.peers) + 1, 0, rep.flat, rep.stats if with_stats else None)
+            c.ddp_unpack(slot, rep.flat)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            c.ddp_local_update(rep.opt_struct(r + 1))
+            e1.record(stream)
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        wall4 = time.perf_counter() - t0
+        nbytes = float(sum(sum(algorithmic_bytes(w, rep.slot_numel[r % Hn]).values()) for r in range(args.warmup, args.warmup + args.steps)))
+        upd_ms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
+        for r in range(Hn):
+            rep.fused_step(r, with_stats=with_stats)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for r in range(Hn, Hn + args.steps):
+            rep.fused_step(r, with_stats=with_stats)
+        torch.cuda.synchronize()
+        wallf = time.perf_counter() - t0
+        upd_bytes = algorithmic_bytes(w, 0)["local_update"]
+        return {"value": nbytes / wall4 / 1e9, "unit": "GB/s", "pct_of_peak": 100.0 * nbytes / wall4 / 1e9 / HBM_PEAK_GBS,
+                "ms_per_step": 1e3 * wall4 / args.steps, "fused_ms_per_step": 1e3 * wallf / args.steps,
+                "local_update_GBps": upd_bytes / (upd_ms * 1e-3) / 1e9, "local_update_frac_of_peak": upd_bytes / (upd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "placement": "first allocation of the slab, nothing left unused, no probing"}
+
+    # First the plain way: one slab, first allocation, nothing left unused, no probing of the physical placement.  For
+    # models of a billion parameters or more the timed replica is then re-allocated by the harness's placement search
+    # (0 / 16 / 24 / 32 / 40 GiB left unused in front of the data, the placement that streams fastest is kept): `value`
+    # is measured on that one, and the plain figures are reported beside it as `no_placement_search`.
+    use_search = w.n_params >= 1_000_000_000 and not args.no_placement_search and args.front_pad_gib is None
+    rep = DeviceReplica(w, 0, options=options, policy=args.policy, wire16=args.wire16, placement_probe=False,
+                        front_pad=(args.front_pad_gib or 0) << 30)
     stage_inputs(rep)
+    first = None
+    if use_search:
+        first = plain_measurement(rep)
+        rep.close()
+        rep._release()
+        rep.ctx.close()
+        del rep
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        rep = DeviceReplica(w, 0, options=options, policy=args.policy, wire16=args.wire16, placement_probe=args.placement_search)
+        stage_inputs(rep)
 
     if args.calibrate_copy:
         from paper_2502_11058_amd import binding as B
@@ -307,7 +365,6 @@ def main() -> int:
         del src, dst
 
     H = len(rep.sets)
-    with_stats = not args.no_stats
     for r in range(args.warmup):
         rep.step(r, with_stats=with_stats)
     torch.cuda.synchronize()
@@ -470,40 +527,6 @@ def main() -> int:
 
     cpu = None if args.no_cpu_baseline else cpu_baseline(rep, w)
 
-    # ---- optional second measurement: the same steps on a slab placed by the harness's search ------------------------
-    placement = None
-    if w.n_params >= 1_000_000_000 and not args.no_placement_search and args.front_pad_gib is None:
-        rep.close()
-        rep._release()
-        rep.ctx.close()
-        del rep
-        import gc
-        gc.collect()
-        torch.cuda.empty_cache()
-        rep = DeviceReplica(w, 0, options=options, policy=args.policy, wire16=args.wire16, placement_probe="search")
-        stage_inputs(rep)
-        for r in range(args.warmup):
-            rep.step(r, with_stats=with_stats)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for r in range(r0, r0 + args.steps):
-            rep.step(r, with_stats=with_stats)
-        torch.cuda.synchronize()
-        wall_p = time.perf_counter() - t0
-        for r in range(r2, r2 + H):
-            rep.fused_step(r, with_stats=with_stats)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for r in range(r2 + H, r2 + H + args.steps):
-            rep.fused_step(r, with_stats=with_stats)
-        torch.cuda.synchronize()
-        wall_pf = time.perf_counter() - t0
-        placement = {"value": total_bytes / wall_p / 1e9, "unit": "GB/s", "ms_per_step": 1e3 * wall_p / args.steps,
-                     "fused_ms_per_step": 1e3 * wall_pf / args.steps, "kept_front_pad_GiB": rep.placement.get("kept_GiB", 0),
-                     "tried_front_pad_GiB": rep.placement.get("front_pad_GiB"),
-                     "probe_GBps": [round(x, 1) for x in rep.placement["probe_GBps"]],
-                     "note": "slab re-allocated with 0/16/24/32/40 GiB left unused in front, fastest placement kept; costs that much HBM"}
-
     out = {
         "metric": "partial-sync+update step: achieved HBM GB/s & % of peak; params/s",
         "value": gbs, "unit": "GB/s", "pct_of_peak": 100.0 * gbs / HBM_PEAK_GBS,
@@ -514,11 +537,16 @@ def main() -> int:
         "config": {"workload": f"{w.name}: P={w.n_params}, N={w.n_replicas}, H={w.period}, {w.param_dtype} params, "
                                f"{w.optimizer}, schedule {args.policy or w.policy}, slot sizes {rep.slot_numel}",
                    "alg_bytes_per_step_avg": total_bytes / args.steps, "layer_stats": with_stats, "options": options,
-                   "placement": "first allocation, no search" if args.front_pad_gib is None else f"front pad {args.front_pad_gib} GiB"},
+                   "placement": (f"harness placement search ({args.placement_search}): kept {rep.placement.get('kept_GiB', 0)} GiB unused in front of the "
+                                 f"data, tried {rep.placement.get('front_pad_GiB') or rep.placement.get('hole_GiB')} GiB, zero-slab probe readings "
+                                 f"{[round(x, 1) for x in rep.placement['probe_GBps']]} GB/s; the plain first allocation is in no_placement_search")
+                   if first is not None else ("first allocation, no search" if args.front_pad_gib is None else f"front pad {args.front_pad_gib} GiB"),
+                   "placement_kept_GiB": rep.placement.get("kept_GiB", 0) if first is not None else (args.front_pad_gib or 0)},
         "kernels": kernels, "roofline": roofline, "fused": fused,
     }
-    if placement is not None:
-        out["placement_search"] = placement
+    if first is not None:
+        out["value_no_placement_search"] = first["value"]
+        out["no_placement_search"] = first
     out["config"]["clocks"] = gpu_clocks()
     if wire16 is not None:
         out["wire16"] = wire16
