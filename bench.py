@@ -8,10 +8,14 @@ N-1 peer buffers, the gradients and all optimizer state already resident in HBM.
 synthetic (shapes of the named model, Gaussian values).  Prints ONE JSON line.
 
   value      = algorithmic bytes of the K timed steps / wall time of the K steps, in GB/s (whole step, launch
-               gaps included); also given as a fraction of the 8 TB/s peak and as parameters per second.
+               gaps included); also given as a fraction of the 8 TB/s peak and as parameters per second.  For models of
+               a billion parameters or more the timed slab is the one the harness's placement search kept; the same K
+               steps on the plain first allocation are measured first and reported as no_placement_search.
   roofline   = the dominant kernel (the fused optimizer update): algorithmic bytes per launch / its average
-               duration measured with events on the launch stream in a second pass of K steps.
-  cpu_baseline = the CPU oracle timed on this machine's host cores on a bounded sample (one transformer block).
+               duration measured with events on the launch stream in a second pass of K steps; traffic = HBM bytes per
+               launch from an earlier rocprofv3 counter run (profiles/traffic.json).
+  cpu_baseline = the CPU oracle timed on this machine's host cores on a bounded sample (one transformer block), with one
+               thread and with all cores.
 """
 from __future__ import annotations
 

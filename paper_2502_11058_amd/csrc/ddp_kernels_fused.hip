@@ -170,10 +170,17 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
                 if constexpr (W16) loc = bf16_widen4(bf16_rne4(pl));
                 auto term = [&](int k) -> f32x4 { return k == lr ? loc : wire4<W16, NT>(a.x[k], vfo + v); };
                 f32x4 acc{};
-                for (int k = 0; k < nrep; ++k) {
-                    const f32x4 x = term(k);
-                    if constexpr (STATS) stage[k * vt + tid] = x;
-                    acc = k == 0 ? x : acc + x;
+                for (int k0 = 0; k0 < nrep; k0 += 8) {  // eight peers in flight, then park and add them in rank order
+                    f32x4 x[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (k0 + j < nrep) x[j] = term(k0 + j);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (k0 + j < nrep) {
+                            if constexpr (STATS) stage[(k0 + j) * vt + tid] = x[j];
+                            acc = k0 + j == 0 ? x[j] : acc + x[j];
+                        }
                 }
                 f32x4 m = acc * inv_n;
                 if constexpr (STATS) {

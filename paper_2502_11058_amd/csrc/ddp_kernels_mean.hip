@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
         if (tid < vt) {
             for (int v = tid; v < nv; v += vt) {
                 f32x4 acc{};
-                for (int k0 = 0; k0 < nrep; k0 += 4) {  // four loads in flight, then park and add them in rank order
+                for (int k0 = 0; k0 < nrep; k0 += 4) {  // four loads in flight (eight measured slower here), then park and add them in rank order
                     f32x4 x[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
@@ -257,6 +257,7 @@ int launch_mean(const MeanLaunch &a, void *stream) {
     int rc;
     if (a.wire16) {
         switch (a.n_replicas) {
+            case 2: rc = launch_mean16_n<2>(ma, a, stream); break;
             case 4: rc = launch_mean16_n<4>(ma, a, stream); break;
             case 8: rc = launch_mean16_n<8>(ma, a, stream); break;
             case 16: rc = launch_mean16_n<16>(ma, a, stream); break;
@@ -272,6 +273,13 @@ int launch_mean(const MeanLaunch &a, void *stream) {
             case 6: rc = launch_mean_n<6>(ma, a, stream); break;
             case 7: rc = launch_mean_n<7>(ma, a, stream); break;
             case 8: rc = launch_mean_n<8>(ma, a, stream); break;
+            case 9: rc = launch_mean_n<9>(ma, a, stream); break;
+            case 10: rc = launch_mean_n<10>(ma, a, stream); break;
+            case 11: rc = launch_mean_n<11>(ma, a, stream); break;
+            case 12: rc = launch_mean_n<12>(ma, a, stream); break;
+            case 13: rc = launch_mean_n<13>(ma, a, stream); break;
+            case 14: rc = launch_mean_n<14>(ma, a, stream); break;
+            case 15: rc = launch_mean_n<15>(ma, a, stream); break;
             case 16: rc = launch_mean_n<16>(ma, a, stream); break;
             default: rc = launch_mean_n<0>(ma, a, stream); break;
         }

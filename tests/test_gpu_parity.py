@@ -315,6 +315,20 @@ def test_maximum_replica_count(oracle, fused, wire16):
     assert t.frac() == 1.0
 
 
+@pytest.mark.parametrize("n_replicas", [1, 2, 6, 7, 9, 10, 11, 12, 13, 14, 15, 17, 18, 24, 32])
+def test_every_compiled_and_run_time_replica_count(oracle, n_replicas):
+    # the averaging kernel is compiled for N = 1..16 and the fused kernels for N = 2, 4, 8, 16; every other count takes the
+    # run-time loop that stages the replicas in LDS.  Four calls, fused, and bf16 on the wire, on ragged shapes.
+    w = W.odd(optimizer="adamw", param_dtype="bf16", n_replicas=n_replicas, period=2)
+    for fused, wire16 in ((False, False), (True, False), (False, True), (True, True)):
+        t = run_trajectory(oracle, w, fused=fused, wire16=wire16, iters=2, arena_offset=n_replicas % 4)
+        assert t.frac() == 1.0
+    w = W.small_llama(n_replicas=n_replicas, period=2)      # dense arenas: the table-free fused path where it applies
+    for fused in (False, True):
+        t = run_trajectory(oracle, w, fused=fused, iters=2)
+        assert t.frac() == 1.0
+
+
 @pytest.mark.parametrize("fused", [False, True])
 def test_many_small_layers(oracle, fused):
     # 240 layers of two small tensors each: long tables, one statistics row per layer, slots of 48 layers
