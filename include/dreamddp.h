@@ -18,6 +18,10 @@
  *     All device memory passed in is owned by the caller and must stay valid while the context uses it.
  *   - The four per-iteration calls only enqueue kernels on the caller's stream (a hipStream_t passed as
  *     void*, NULL = the default stream).  They never allocate, free, copy to the host or synchronise.
+ *   - A context holds nothing of the training state: only tables derived from the registration and the schedule, and a
+ *     reduction scratch that every call writes before it reads.  Parameters, optimizer state, model copy and the step
+ *     counter (ddp_opt.step) are the caller's: a checkpoint is those tensors plus the iteration number, and a new
+ *     context registered over the restored tensors continues with the bits of the uninterrupted run.
  *   - A context is not thread-safe; calls that share a context or device buffers must be ordered by the caller
  *     (stream order is enough): the statistics go through one reduction scratch per context.  The only calls that
  *     may be in flight together on one context are the layer-range calls, for disjoint ranges.

@@ -15,8 +15,13 @@ CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(LIB_DIR, "libdreamddp.so")
-SOURCES = ["ddp_schedule.cpp", "ddp_context.hip", "ddp_noalloc.hip", "ddp_probe.hip", "ddp_stream.hip", "ddp_kernels_copy.hip", "ddp_kernels_mean.hip",
-           "ddp_kernels_update.hip", "ddp_kernels_fused.hip", "ddp_kernels_fused_dense.hip"]
+# (source, object name, extra flags); the table-driven fused kernel has the most instantiations and is built in two halves
+SOURCES = [("ddp_kernels_fused.hip", "ddp_kernels_fused_adamw", ["-DDDP_FUSED_ADAM=1"]),
+           ("ddp_kernels_fused.hip", "ddp_kernels_fused_sgdm", ["-DDDP_FUSED_ADAM=0"]),
+           ("ddp_kernels_fused_dense.hip", "ddp_kernels_fused_dense", []), ("ddp_kernels_mean.hip", "ddp_kernels_mean", []),
+           ("ddp_kernels_update.hip", "ddp_kernels_update", []), ("ddp_kernels_copy.hip", "ddp_kernels_copy", []),
+           ("ddp_context.hip", "ddp_context", []), ("ddp_noalloc.hip", "ddp_noalloc", []), ("ddp_probe.hip", "ddp_probe", []),
+           ("ddp_stream.hip", "ddp_stream", []), ("ddp_schedule.cpp", "ddp_schedule", [])]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -52,8 +57,8 @@ def build(verbose: bool = False, jobs: int = 0) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     jobs = jobs or min(len(SOURCES), max(1, len(os.sched_getaffinity(0))))
-    objs = [os.path.join(OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in SOURCES]
-    cmds = [[hipcc] + FLAGS + ["-x", "hip", "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    objs = [os.path.join(OBJ_DIR, name + ".o") for _, name, _ in SOURCES]
+    cmds = [[hipcc] + FLAGS + extra + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", o] for (src, _, extra), o in zip(SOURCES, objs)]
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         list(ex.map(lambda c: _run(c, verbose), cmds))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose)

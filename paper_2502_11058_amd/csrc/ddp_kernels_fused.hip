@@ -1,5 +1,12 @@
 // fused synchronisation + update, table-driven (both cases of Eq. (5) in one pass).
+//
+// Compiled twice, once per optimizer (-DDDP_FUSED_ADAM=0: SGD with momentum, =1: AdamW), so that the two halves of the
+// kernel's instantiations build in parallel; the first half also holds the dispatcher.
 #include "ddp_device.h"
+
+#ifndef DDP_FUSED_ADAM
+#error "compile with -DDDP_FUSED_ADAM=0 or -DDDP_FUSED_ADAM=1"
+#endif
 
 namespace ddp {
 namespace {
@@ -230,11 +237,20 @@ static int launch_fused_t(const FusedLaunch &f, const FusedArgs &fa, void *strea
         case 4: return launch_fused_n<A, G, M, 4>(f, fa, stream);
         case 8: return launch_fused_n<A, G, M, 8>(f, fa, stream);
         case 16: return launch_fused_n<A, G, M, 16>(f, fa, stream);
+        case 32: return launch_fused_n<A, G, M, 32>(f, fa, stream);
         default: return launch_fused_n<A, G, M, 0>(f, fa, stream);
     }
 }
 
-int launch_fused(const FusedLaunch &f, void *stream) {
+#if DDP_FUSED_ADAM
+#define DDP_FUSED_HALF launch_fused_adamw
+#else
+#define DDP_FUSED_HALF launch_fused_sgdm
+#endif
+
+// The kernel launch of this file's optimizer (no statistics reduction).
+int DDP_FUSED_HALF(const FusedLaunch &f, void *stream) {
+    constexpr bool A = DDP_FUSED_ADAM != 0;
     FusedArgs fa{};
     for (int k = 0; k < f.n_replicas; ++k) fa.x[k] = f.x[k];
     fa.tensors = f.tensors;
@@ -248,21 +264,21 @@ int launch_fused(const FusedLaunch &f, void *stream) {
     fa.local_rank = f.local_rank;
     fa.chunk_elems = f.chunk_elems;
     fa.stage_threads = stage_threads(f.n_replicas);
-    const bool adam = f.kind == DDP_OPT_ADAMW, gb = f.grad_dtype == DDP_BF16, md = f.with_model;
-    int rc = (int)hipErrorInvalidValue;
-#define DDP_F(A, G, M) \
-    if (adam == A && gb == G && md == M) rc = launch_fused_t<A, G, M>(f, fa, stream);
-    DDP_F(false, false, false)
-    DDP_F(false, false, true)
-    DDP_F(false, true, false)
-    DDP_F(false, true, true)
-    DDP_F(true, false, false)
-    DDP_F(true, false, true)
-    DDP_F(true, true, false)
-    DDP_F(true, true, true)
-#undef DDP_F
+    const bool gb = f.grad_dtype == DDP_BF16, md = f.with_model;
+    if (!gb && !md) return launch_fused_t<A, false, false>(f, fa, stream);
+    if (!gb && md) return launch_fused_t<A, false, true>(f, fa, stream);
+    if (gb && !md) return launch_fused_t<A, true, false>(f, fa, stream);
+    return launch_fused_t<A, true, true>(f, fa, stream);
+}
+
+#if !DDP_FUSED_ADAM
+int launch_fused_adamw(const FusedLaunch &f, void *stream);
+
+int launch_fused(const FusedLaunch &f, void *stream) {
+    const int rc = f.kind == DDP_OPT_ADAMW ? launch_fused_adamw(f, stream) : launch_fused_sgdm(f, stream);
     if (rc != 0 || !f.partials) return rc;
     return launch_stats(f.partials, f.slice_sums, f.layer_ranges, f.n_layers, f.n_replicas, f.stats, f.max_partials_per_layer, stream);
 }
+#endif
 
 }  // namespace ddp

@@ -91,7 +91,7 @@ static int launch_fused_dense_n(const FusedDenseLaunch &f, const FusedDenseArgs 
 #undef DDP_FUSED
 }
 
-bool fused_dense_supports(int n_replicas) { return n_replicas == 2 || n_replicas == 4 || n_replicas == 8 || n_replicas == 16; }
+bool fused_dense_supports(int n_replicas) { return n_replicas == 2 || n_replicas == 4 || n_replicas == 8 || n_replicas == 16 || n_replicas == 32; }
 
 int launch_fused_dense(const FusedDenseLaunch &f, void *stream) {
     if (f.d.n <= 0) return 0;
@@ -118,6 +118,7 @@ int launch_fused_dense(const FusedDenseLaunch &f, void *stream) {
             case 4: return launch_fused_dense_n<A, G, M, 4>(f, fa, grid, stream);                       \
             case 8: return launch_fused_dense_n<A, G, M, 8>(f, fa, grid, stream);                       \
             case 16: return launch_fused_dense_n<A, G, M, 16>(f, fa, grid, stream);                     \
+            case 32: return launch_fused_dense_n<A, G, M, 32>(f, fa, grid, stream);                     \
             default: return (int)hipErrorInvalidValue;                                                  \
         }
     DDP_F(false, false, false)

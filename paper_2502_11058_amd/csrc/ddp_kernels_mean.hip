@@ -68,7 +68,9 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
     };
 
     if constexpr (NREP > 0) {
-        constexpr int B = 2;  // vectors per thread in flight: 2 * NREP loads (a 2048-element chunk is 2 vectors per thread)
+        // vectors per thread in flight: 2 * NREP loads (a 2048-element chunk is 2 vectors per thread); beyond 16 replicas one
+        // vector, so that the loads still fit the register file
+        constexpr int B = NREP > 16 ? 1 : 2;
         auto rep4 = [&](int k, int idx) -> f32x4 { return wire4<W16, NT>(a.x[k], vbase + idx); };
         auto put4 = [&](int idx, f32x4 m) { st<NT>(o4 + idx, m); };
         int v = tid;
@@ -261,6 +263,7 @@ int launch_mean(const MeanLaunch &a, void *stream) {
             case 4: rc = launch_mean16_n<4>(ma, a, stream); break;
             case 8: rc = launch_mean16_n<8>(ma, a, stream); break;
             case 16: rc = launch_mean16_n<16>(ma, a, stream); break;
+            case 32: rc = launch_mean16_n<32>(ma, a, stream); break;
             default: rc = launch_mean16_n<0>(ma, a, stream); break;
         }
     } else {
@@ -281,6 +284,7 @@ int launch_mean(const MeanLaunch &a, void *stream) {
             case 14: rc = launch_mean_n<14>(ma, a, stream); break;
             case 15: rc = launch_mean_n<15>(ma, a, stream); break;
             case 16: rc = launch_mean_n<16>(ma, a, stream); break;
+            case 32: rc = launch_mean_n<32>(ma, a, stream); break;
             default: rc = launch_mean_n<0>(ma, a, stream); break;
         }
     }

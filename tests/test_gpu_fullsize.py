@@ -27,6 +27,14 @@ def test_tinyllama_full_trajectory(oracle):
 
 
 @pytest.mark.timeout(900)
+def test_tinyllama_bf16_wire_update_then_sync_every_element(oracle):
+    # the other branch of every choice the step has, at 1.1 G parameters, every element against the oracle: the fused
+    # entry point, bf16 on the wire, and Eq. (5)'s printed order (optimizer step first, then the average)
+    t = run_trajectory(oracle, W.tinyllama_1b(), iters=2, check_every=2, fused=True, wire16=True, order=1)
+    assert t.frac() == 1.0
+
+
+@pytest.mark.timeout(900)
 def test_tinyllama_sampled_16_iterations(oracle):
     # four periods with a million carried samples: the update's tolerance is stated after 16 iterations
     assert run_sampled(oracle, W.tinyllama_1b(), iters=16) == 1.0
