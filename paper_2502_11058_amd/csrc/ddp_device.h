@@ -90,6 +90,20 @@ __device__ __forceinline__ f32x4 wire4(const void *base, int64_t v) {
         return ld<NT>(reinterpret_cast<const f32x4 *>(base) + v);
 }
 
+// A group of four elements of a replica as it sits in memory, and its exact widening to fp32.
+template <bool W16>
+struct WireVec;
+template <>
+struct WireVec<false> {
+    typedef f32x4 type;
+    static __device__ __forceinline__ f32x4 widen(f32x4 v) { return v; }
+};
+template <>
+struct WireVec<true> {
+    typedef u16x4 type;
+    static __device__ __forceinline__ f32x4 widen(u16x4 v) { return bf16_widen4(v); }
+};
+
 // Buffer (MUBUF) accesses: a per-workgroup descriptor (base in SGPRs, extent = the workgroup's part of the stream)
 // plus a 32-bit byte offset per lane.  Accesses past the extent read zero / are dropped by the hardware.
 // AUX: cache policy bits of the instruction (2 = nt, the streaming hint; 0 = default).

@@ -71,40 +71,42 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
         // vectors per thread in flight: 2 * NREP loads (a 2048-element chunk is 2 vectors per thread); beyond 16 replicas one
         // vector, so that the loads still fit the register file
         constexpr int B = NREP > 16 ? 1 : 2;
-        auto rep4 = [&](int k, int idx) -> f32x4 { return wire4<W16, NT>(a.x[k], vbase + idx); };
+        // a replica's vector as it sits in memory: kept in that form (bf16: half the registers) until it is used
+        typedef typename WireVec<W16>::type raw4;
+        auto rep4 = [&](int k, int idx) -> raw4 { return ld<NT>(reinterpret_cast<const raw4 *>(a.x[k]) + vbase + idx); };
         auto put4 = [&](int idx, f32x4 m) { st<NT>(o4 + idx, m); };
         int v = tid;
         for (; v + (B - 1) * kThreads < nv; v += B * kThreads) {
-            f32x4 x[B][NREP];
+            raw4 x[B][NREP];
 #pragma unroll
             for (int b = 0; b < B; ++b)
 #pragma unroll
                 for (int k = 0; k < NREP; ++k) x[b][k] = rep4(k, v + b * kThreads);
 #pragma unroll
             for (int b = 0; b < B; ++b) {
-                f32x4 acc = x[b][0];
+                f32x4 acc = WireVec<W16>::widen(x[b][0]);
 #pragma unroll
-                for (int k = 1; k < NREP; ++k) acc = acc + x[b][k];
+                for (int k = 1; k < NREP; ++k) acc = acc + WireVec<W16>::widen(x[b][k]);
                 const f32x4 m = acc * inv_n;
                 if constexpr (STATS) {
 #pragma unroll
-                    for (int k = 0; k < NREP; ++k) stats4(m, x[b][k]);
+                    for (int k = 0; k < NREP; ++k) stats4(m, WireVec<W16>::widen(x[b][k]));
                     msq4(m);
                 }
                 put4(v + b * kThreads, m);
             }
         }
         for (; v < nv; v += kThreads) {
-            f32x4 x[NREP];
+            raw4 x[NREP];
 #pragma unroll
             for (int k = 0; k < NREP; ++k) x[k] = rep4(k, v);
-            f32x4 acc = x[0];
+            f32x4 acc = WireVec<W16>::widen(x[0]);
 #pragma unroll
-            for (int k = 1; k < NREP; ++k) acc = acc + x[k];
+            for (int k = 1; k < NREP; ++k) acc = acc + WireVec<W16>::widen(x[k]);
             const f32x4 m = acc * inv_n;
             if constexpr (STATS) {
 #pragma unroll
-                for (int k = 0; k < NREP; ++k) stats4(m, x[k]);
+                for (int k = 0; k < NREP; ++k) stats4(m, WireVec<W16>::widen(x[k]));
                 msq4(m);
             }
             put4(v, m);

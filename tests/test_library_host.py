@@ -223,3 +223,26 @@ def test_filled_workload_schedules(oracle, name):
         it0, ex0, per0 = B.ddp_schedule_time_model(fp, bp, comm, sp, sl)
         it1, ex1, per1 = B.ddp_schedule_time_model(fp, bp, comm, osp, osl)
         assert (it1.tolist(), ex1.tolist(), per1) == oracle.time_model(fp, bp, comm, B.sets_from_csr(osp, osl))
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    """include/dreamddp.h compiles as strict C99 and a C program linked against the shared library calls the scheduler."""
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.dirname(B.LIB_PATH)
+    exe = str(tmp_path / "schedule_from_c")
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I" + os.path.join(root, "include"),
+           os.path.join(root, "tests", "c_abi", "schedule_from_c.c"), "-L" + libdir, "-ldreamddp", "-Wl,-rpath," + libdir,
+           "-Wl,--allow-shlib-undefined", "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    env = dict(os.environ, LD_LIBRARY_PATH=os.pathsep.join(filter(None, ["/opt/rocm/lib", os.environ.get("LD_LIBRARY_PATH", "")])))
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    lines = r.stdout.strip().splitlines()
+    assert lines[0] == "policy 5 cost 33 sets 4 3 2 | 1 0 period 33"
+    assert lines[1] == "policy 4 cost 26 sets 4 | 3 2 1 0 period 33"       # Eq. (7) charges each communication from its own layer's BP on
+    assert lines[2].startswith("error: ddp_schedule")
