@@ -21,7 +21,7 @@ from . import workloads as W
 class DeviceReplica:
     def __init__(self, w: W.Workload, device: int = 0, options: Optional[Dict[str, int]] = None, arena_offset: int = 0,
                  grad_dtype: Optional[str] = None, policy: Optional[str] = None, n_peers: Optional[int] = None,
-                 region_skew: int = 0, placement_probe=None, wire16: bool = False, front_pad: int = 0):
+                 region_skew: int = 0, placement_probe=None, wire16: bool = False, front_pad: int = 0, flat_capacity: int = 0):
         """Schedules, allocates, registers.  arena_offset: elements skipped at the start of every arena (tests use
         it to break 16-byte alignment).  policy: schedule policy (default: the workload's).  region_skew: extra bytes
         (multiple of 256) by which each successive region of the slab is shifted off its 2 MiB boundary.
@@ -29,6 +29,8 @@ class DeviceReplica:
         physical memory that streams faster, keep that one (default: on for models of a billion parameters or more).
         front_pad: bytes (multiple of 2 MiB) left unused at the start of the slab; placement_probe="search" tries
         several values and keeps the one whose physical placement streams fastest.
+        flat_capacity: elements the flat and peer buffers hold at least (default: the largest slot of the initial schedule);
+        a worker that will be re-scheduled (install_schedule) reserves the largest slot it may ever get.
         wire16: also allocate bf16 flat and peer buffers for the bf16-on-the-wire entry points (step/fused_step then
         take wire16=True)."""
         self.wire16 = wire16
@@ -55,7 +57,7 @@ class DeviceReplica:
         self.set_ptr, self.set_layers = sp, sl
         self.sets = B.sets_from_csr(sp, sl)
         lay = w.layer_numel()
-        smax = max(max(sum(lay[l] for l in S) for S in self.sets), 4)
+        smax = max(max(sum(lay[l] for l in S) for S in self.sets), 4, int(flat_capacity))
         n_peers = w.n_replicas - 1 if n_peers is None else n_peers
         max_layers = max(len(S) for S in self.sets)
 
@@ -182,7 +184,7 @@ class DeviceReplica:
         if self.wire16:
             regions.append(("flat16", torch.bfloat16, smax))
             regions += [(f"peer16_{k}", torch.bfloat16, smax) for k in range(n_peers)]
-        regions.append(("stats", torch.float64, 2 * max_layers + 2))
+        regions.append(("stats", torch.float64, 2 * max(max_layers, w.n_layers) + 2))
         ALIGN = 2 << 20
         pos, place = self.front_pad, {}
         for j, (name, dt, n) in enumerate(regions):
@@ -225,7 +227,7 @@ class DeviceReplica:
                                     B.DDP_BF16 if self.grad_bf16 else B.DDP_F32, self.sync, self.model, self.grad, self.s0, self.s1)
         self.ctx.ddp_set_schedule(sp, sl)
         self.slot_numel = [self.ctx.ddp_slot_numel(s) for s in range(len(self.sets))]
-        assert max(max(self.slot_numel), 4) == smax
+        assert max(max(self.slot_numel), 4) <= smax
 
     # -- seeded inputs (harness work, outside any timed region) ---------------------------------------------
     def init_params(self) -> None:
@@ -328,6 +330,24 @@ class DeviceReplica:
                                                   local_rank, self.stats if with_stats else None, opt, side_stream)
             hi = lo
         main.wait_stream(side_stream)
+
+    def install_schedule(self, set_ptr, set_layers) -> None:
+        """Replace the schedule (output of ddp_schedule, e.g. after re-profiling the layer times): ddp_set_schedule rebuilds
+        the per-slot tables.  The flat and peer buffers must hold the largest new slot (flat_capacity)."""
+        sets = B.sets_from_csr(set_ptr, set_layers)
+        lay = self.w.layer_numel()
+        need = max(sum(lay[l] for l in S) for S in sets)
+        if need > self.flat.numel():
+            raise ValueError(f"the new schedule has a slot of {need} elements, the flat and peer buffers hold {self.flat.numel()}")
+        if max(len(S) for S in sets) * 2 > self.stats.numel():
+            raise ValueError("the statistics buffer is too small for the new schedule")
+        self.ctx.ddp_set_schedule(set_ptr, set_layers)
+        self.set_ptr, self.set_layers, self.sets = set_ptr, set_layers, sets
+        self.slot_numel = [self.ctx.ddp_slot_numel(s) for s in range(len(sets))]
+
+    def layer_wire_bytes(self, wire16: bool = False) -> List[int]:
+        """Bytes each layer puts on the wire when it is synchronised (what its communication time is proportional to)."""
+        return [(2 if wire16 else 4) * n for n in self.w.layer_numel()]
 
     def close(self) -> None:
         self.ctx.close()

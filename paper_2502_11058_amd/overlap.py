@@ -60,6 +60,10 @@ class BackwardOverlap:
             self.params.append(p)
             self._tensors_in_layer[l] += 1
         self._left: Optional[List[int]] = None
+        self._profile = False
+        self._stamps = {}
+        self._stamp_order: List[int] = []
+        self._bp_start = None
         self._launched: List[bool] = []
         self.launch_order: List[int] = []       # layers in the order their calls were enqueued (last iteration)
 
@@ -72,11 +76,20 @@ class BackwardOverlap:
             self._owned = []
 
     def begin(self, r: int, local_rank: int = 0, with_stats: bool = True, wire16: bool = False,
-              order: int = B.DDP_SYNC_THEN_UPDATE) -> None:
+              order: int = B.DDP_SYNC_THEN_UPDATE, profile: bool = False) -> None:
         """Start iteration r (0-based): clear the gradients (autograd accumulates) and arm the hooks.  Whatever is
         already queued on the current stream (peer buffers, the previous iteration) is ordered before the side
-        stream's work."""
+        stream's work.
+
+        profile=True makes this a profiling iteration (the paper's profiler, Sec. 3.2: per-layer backward times are the
+        scheduler's input): the hooks only time-stamp each layer's finished gradient, and every layer's sync + update call
+        is made in end(), after the backward pass, so that nothing runs beside the backward kernels while they are timed.
+        The result of the iteration is the same.  Call backward through `self.backward(loss)` so that the start is
+        stamped too, then read `layer_bp_ns()` after `end()`."""
         rep = self.rep
+        self._profile = profile
+        self._stamps = {}
+        self._bp_start = None
         rep.a_grad.zero_()
         self._slot = r % len(rep.sets)
         self._opt = rep.opt_struct(r + 1)
@@ -97,7 +110,34 @@ class BackwardOverlap:
         if self._left[l] == 0:
             self._launch(l)
 
+    def backward(self, loss: torch.Tensor) -> None:
+        """loss.backward() with the start of the backward pass time-stamped on the current stream (profiling iterations)."""
+        if self._profile:
+            self._bp_start = torch.cuda.Event(enable_timing=True)
+            self._bp_start.record(torch.cuda.current_stream())
+        loss.backward()
+
+    def layer_bp_ns(self) -> List[int]:
+        """Per-layer backward time of the last profiling iteration in integer nanoseconds, indexed by layer id: the time
+        between the completion of a layer's gradients and the completion of the layer finished before it (for the first
+        one: since the start of the backward pass).  Synchronises the device.  Layers that took no part in the graph get 0."""
+        if not self._stamps or self._bp_start is None:
+            raise RuntimeError("no profiling iteration recorded: begin(profile=True), backward(loss), end()")
+        torch.cuda.synchronize(self.rep.dev)
+        out = [0] * self.rep.w.n_layers
+        prev = self._bp_start
+        for l in self._stamp_order:
+            out[l] = max(0, int(round(prev.elapsed_time(self._stamps[l]) * 1e6)))
+            prev = self._stamps[l]
+        return out
+
     def _launch(self, l: int) -> None:
+        if self._profile and self._left is not None:
+            # profiling iteration: time-stamp the finished gradient, the call itself waits for end()
+            ev = torch.cuda.Event(enable_timing=True)
+            ev.record(torch.cuda.current_stream())
+            self._stamps[l] = ev
+            return
         # the hook runs on the stream the backward pass runs on: everything that produced this layer's gradients
         # precedes the event
         ready = torch.cuda.Event()
@@ -111,8 +151,9 @@ class BackwardOverlap:
     def end(self) -> None:
         """After backward: layers whose parameters took no part in the graph get their call now (their gradient is
         zero), then the current stream waits for the side stream, so the next forward sees the new parameters."""
+        self._stamp_order = list(self._stamps)      # dicts keep insertion order: the order the layers finished in
+        self._left = None                           # from here on _launch makes the calls, also in a profiling iteration
         for l in range(self.rep.w.n_layers - 1, -1, -1):
             if not self._launched[l]:
                 self._launch(l)
-        self._left = None
         torch.cuda.current_stream().wait_stream(self.side)

@@ -101,3 +101,65 @@ def test_autograd_hooks_drive_the_layerwise_calls(oracle, wire16, order, policy,
     assert all(np.isfinite(losses))
     ov.close()
     rep.close()
+
+
+def test_profiled_layer_times_feed_the_scheduler(oracle):
+    """Sec. 3.2-3.3 as a loop: profile the per-layer backward times of the user's model, hand them (with communication
+    times from the layers' wire bytes and an assumed bandwidth) to ddp_schedule, install the result at a period boundary
+    and go on training.  The schedule must be the exhaustive optimum for the measured times, and the trajectory must stay
+    bit-identical to the oracle's, which is told the same sets."""
+    from paper_2502_11058_amd import binding as B
+    from paper_2502_11058_amd.harness import DeviceReplica
+    from paper_2502_11058_amd.overlap import BackwardOverlap
+    assert torch.cuda.is_available(), "no GPU visible: the HIP path cannot run (there is no CPU fallback)"
+    w = _workload(4, 3, "enp")
+    L, H, N = w.n_layers, w.period, w.n_replicas
+    rep = DeviceReplica(w, 0, flat_capacity=w.n_params)         # room for any schedule, even all layers in one slot
+    rep.init_params()
+    ov = BackwardOverlap(rep)
+    hyper = dict(lr=w.lr, momentum=w.momentum, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay)
+    wk = oracle.Worker(rep.layer_of, [_np(t) for t in rep.sync], w.optimizer, hyper, True)
+    gen = torch.Generator(device=rep.dev)
+    gen.manual_seed(11)
+    profiles = []
+
+    def iteration(r, profile):
+        S, rank = rep.sets[r % H], r % N
+        off, order_t, total = oracle.slot_offsets(rep.layer_of, rep.numel, S)
+        base = torch.cat([rep.sync[t] for t in order_t]) if total else rep.flat[:0]
+        rep.fill_peers_from(base, r, total)
+        peers_host = [_np(p[:total]) for p in rep.peers]
+        tokens = torch.randint(0, VOCAB, (T,), device=rep.dev, generator=gen)
+        targets = torch.randint(0, VOCAB, (T,), device=rep.dev, generator=gen)
+        torch.cuda.synchronize()
+        ov.begin(r, local_rank=rank, profile=profile)
+        ov.backward(_loss(ov.params, tokens, targets))
+        ov.end()
+        torch.cuda.synchronize()
+        if profile:
+            profiles.append(ov.layer_bp_ns())
+        wk.sync(S, peers_host, rank)
+        wk.local_update([_np(g) for g in rep.grad], r + 1)
+        for t in range(len(w.tensors)):
+            assert np.array_equal(_np(rep.sync[t]).view(np.uint32), wk.p[t].view(np.uint32)), f"param r={r} t={t}"
+            assert np.array_equal(_np(rep.s1[t]).view(np.uint32), wk.s1[t].view(np.uint32)), f"v r={r} t={t}"
+            assert np.array_equal(_np(rep.model[t]), wk.model[t]), f"model copy r={r} t={t}"
+
+    for r in range(H):                                           # the first period on the initial ENP schedule, profiled after a warm-up
+        iteration(r, profile=r > 0)
+    bp = np.median(np.asarray(profiles, dtype=np.int64), axis=0).astype(np.int64)
+    assert bp.shape == (L,) and (bp > 0).all(), bp               # every layer took part and took time
+    # communication: wire bytes of a layer over a bandwidth that makes the whole model cost two backward passes, so that the
+    # optimum is neither "everything at once" nor trivial
+    nbytes = np.asarray(rep.layer_wire_bytes(), dtype=np.float64)
+    comm = np.rint(nbytes * (2.0 * bp.sum() / nbytes.sum())).astype(np.int64)
+    _, sp, sl, cost = B.ddp_schedule("opt", L, H, None, bp, comm)
+    sets = B.sets_from_csr(sp, sl)
+    assert sets == oracle.schedule("opt", L, H, bp, comm)        # exhaustive search on the measured times
+    assert cost <= B.ddp_schedule("enp", L, H, None, bp, comm)[3]
+    rep.install_schedule(sp, sl)
+    assert rep.sets == sets and sorted(l for S in sets for l in S) == list(range(L))
+    for r in range(H, 3 * H):                                    # two more periods on the new schedule
+        iteration(r, profile=False)
+    ov.close()
+    rep.close()
