@@ -528,3 +528,79 @@ def test_llama2_7b_every_element_of_one_iteration(oracle):
 @pytest.mark.timeout(900)
 def test_llama3_8b_every_element_of_one_iteration(oracle):
     assert run_all_elements(oracle, W.llama3_8b(), warm=2, placement=False, both_paths=False) == 1.0
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("dense_path", [1, 0])
+def test_single_tensor_beyond_2_31_elements(oracle, dense_path):
+    """One tensor of 2^31 + 4099 fp32 elements (an embedding of a very large model has that many): element indices inside
+    a tensor, chunk starts and flat offsets all pass 2^31.  Four calls and then the fused entry point, table-free and
+    table-driven; every element against independent device-side evaluations (exact for pack / average / unpack, and
+    for SGD-momentum written as separate torch operations), samples against the oracle."""
+    from paper_2502_11058_amd.harness import DeviceReplica
+    _need_gpu()
+    gc.collect()
+    torch.cuda.empty_cache()
+    big = (1 << 31) + 4099
+    ts = [W.TensorSpec("small.w", 0, 1000), W.TensorSpec("huge.w", 1, big), W.TensorSpec("huge.b", 1, 3)]
+    w = W.Workload("huge_tensor", ts, n_replicas=2, period=2, optimizer="sgdm", param_dtype="f32", lr=0.01, momentum=0.9,
+                   sigma_drift=1e-3, sigma_grad=1e-2, iterations=2, policy="round_robin")
+    rep = DeviceReplica(w, 0, options={"dense_path": dense_path}, placement_probe=False)
+    rep.init_params()
+    dev = rep.dev
+    P = w.n_params
+    rng = np.random.default_rng(3)
+    gi_host = np.unique(np.concatenate([rng.integers(0, P, 200_000), np.arange(0, 2000), np.arange(P - 2000, P),
+                                        np.arange((1 << 31) - 3000, min(P, (1 << 31) + 6000))]))
+    assert 0 <= gi_host.min() and gi_host.max() < P          # torch's device gather does not check bounds
+    gi = torch.from_numpy(gi_host).to(dev)
+    p_s, b_s = _np(rep.a_sync[gi]), np.zeros(gi_host.size, dtype=np.float32)
+    half = torch.tensor(0.5, dtype=torch.float32, device=dev)
+    for r in range(4):
+        fused = r >= 2
+        slot, S, rank = r % 2, rep.sets[r % 2], r % 2
+        off, order_t, total = oracle.slot_offsets(rep.layer_of, rep.numel, S)
+        assert rep.ctx.ddp_slot_numel(slot) == total
+        rep.fill_grads(r)
+        g_s = _np(rep.a_grad[gi])
+        # where the samples sit in the flat buffer (arenas are dense: tensor t starts at rep.offsets[t])
+        tensor_of = np.searchsorted(rep.offsets, gi_host, side="right") - 1
+        sel = off[tensor_of] >= 0
+        fi = torch.from_numpy((off[tensor_of] + (gi_host - rep.offsets[tensor_of]))[sel]).to(dev)
+        base = torch.cat([rep.sync[t] for t in order_t])
+        rep.fill_peers_from(base, r, total)
+        peer = rep.peers[0]
+        seq = [peer[:total], base] if rank == 1 else [base, peer[:total]]
+        mean_dev = (seq[0] + seq[1]) * half                                    # N = 2: one add, one exact halving
+        x_s = [_np(t_[fi]) for t_ in seq]
+        mean_s = oracle.mean(x_s)
+        assert np.array_equal(_bits(_np(mean_dev[fi])), _bits(mean_s))         # the device evaluation agrees with the oracle where sampled
+        before_p, before_b = rep.a_sync.clone(), rep.a_s0.clone()
+        if fused:
+            del base
+            rep.fused_step(r, rank)
+        else:
+            rep.flat.fill_(float("nan"))
+            rep.ctx.ddp_pack(slot, rep.flat)
+            assert torch.equal(rep.flat[:total].view(torch.int32), base.view(torch.int32)), f"pack r={r}"
+            del base
+            rep.ctx.ddp_partial_average(slot, rep.flat, rep.peers, 2, rank, rep.flat, rep.stats)
+            assert torch.equal(rep.flat[:total].view(torch.int32), mean_dev.view(torch.int32)), f"mean r={r}"
+            rep.ctx.ddp_unpack(slot, rep.flat)
+            rep.ctx.ddp_local_update(rep.opt_struct(r + 1))
+        # every element: synchronised tensors take the mean, then everything takes buf = mu*buf + g; p = p - lr*buf
+        for t in order_t:
+            before_p[int(rep.offsets[t]): int(rep.offsets[t]) + rep.numel[t]] = mean_dev[int(off[t]): int(off[t]) + rep.numel[t]]
+        del mean_dev
+        before_b.mul_(w.momentum).add_(rep.a_grad)
+        before_p.sub_(before_b * w.lr)
+        assert torch.equal(rep.a_s0.view(torch.int32), before_b.view(torch.int32)), f"momentum buffer r={r}"
+        assert torch.equal(rep.a_sync.view(torch.int32), before_p.view(torch.int32)), f"parameters r={r}"
+        del before_p, before_b
+        # samples through the oracle
+        p_s[sel] = mean_s
+        oracle.sgdm(p_s, g_s, b_s, w.lr, w.momentum)
+        assert np.array_equal(_bits(_np(rep.a_sync[gi])), _bits(p_s)), f"oracle samples, parameters r={r}"
+        assert np.array_equal(_bits(_np(rep.a_s0[gi])), _bits(b_s)), f"oracle samples, momentum r={r}"
+        progress(f"[huge_tensor dense_path={dense_path}] r={r} {'fused' if fused else 'four calls'} slot {slot} ({total} elements) ok")
+    rep.close()
