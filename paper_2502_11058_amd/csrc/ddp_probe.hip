@@ -50,8 +50,9 @@ __global__ __launch_bounds__(kThreads) void probe_kernel(const ProbeArgs a) {
         if constexpr (NW == 0) keep = keep + s0 + s1;
     }
     if constexpr (NW == 0) {
-        // never true for finite data; keeps the loads from being removed
-        if (keep.x == 1.2345e38f && keep.y == -7.0f) *static_cast<volatile float *>(const_cast<void *>(a.rd[0])) = keep.z;
+        // a read-only probe has no result to store: hand the accumulated sum to an empty asm statement so that the loads
+        // that feed it cannot be removed
+        asm volatile("" : : "v"(keep.x), "v"(keep.y), "v"(keep.z), "v"(keep.w));
     }
 }
 

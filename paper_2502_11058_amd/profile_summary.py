@@ -109,12 +109,10 @@ def main() -> int:
         print(f"{short(name):100s} {calls:6d} {tot:12.1f} {avg:11.2f} {pct:6.2f}")
     print("\n== the same trace, the library's kernels by grid size (a launch over the whole model vs over a range of layers)")
     print(f"{'kernel':64s} {'workgroups':>11s} {'calls':>6s} {'avg_us':>11s} {'min_us':>11s} {'max_us':>11s}")
-    dur = {}
     for name, grid, calls, avg, mn, mx in tdb.execute(
             "select name, grid_x / workgroup_x, count(*), avg(duration) / 1e3, min(duration) / 1e3, max(duration) / 1e3 from kernels "
             "where name like '%ddp::%' group by name, grid_x order by sum(duration) desc limit 24"):
         print(f"{short(name)[:64]:64s} {grid:11d} {calls:6d} {avg:11.2f} {mn:11.2f} {mx:11.2f}")
-        dur[(name, grid)] = (calls, avg)
 
     fetch, fscale = counter_means(os.path.join(a.out, "fetch"), "FETCH_SIZE")
     write, wscale = counter_means(os.path.join(a.out, "write"), "WRITE_SIZE")

@@ -1,10 +1,14 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times.
 
-TinyLlama-1.1B: the whole 16-iteration trajectory, every element, against the oracle.
-Llama-2-7B (8 iterations) and Llama-3-8B (N = 16, ragged schedule): the oracle carries ~1.1 M sampled parameters
-(random positions plus every tensor boundary and chunk boundaries) through the whole trajectory, one by one;
-on top of that every element is checked on the device against independent gathers / sequential torch sums
-(pack, unpack and the average are exact, so they must agree bit for bit at any size).
+TinyLlama-1.1B: one whole period, every element of every stage, against the oracle (default order and fp32 wire; and
+two iterations through the fused entry point with bf16 on the wire in the update-then-sync order), plus 16 iterations
+with a million carried samples.
+Llama-2-7B and Llama-3-8B (N = 16, ragged schedule): every element of one full iteration against the oracle, streamed
+layer by layer through the host (run_all_elements), and whole trajectories (8 iterations) with ~1.1 M sampled parameters
+carried by the oracle (random positions plus every tensor boundary and chunk boundaries), where on top every element of
+pack, average and unpack is checked on the device against independent gathers / sequential torch sums (those stages are
+exact, so they must agree bit for bit at any size).
+Edge shapes at full size: the whole 7B model in one slot, and a single tensor of more than 2^31 elements.
 """
 import gc
 
