@@ -94,6 +94,7 @@ def main() -> int:
     ap.add_argument("out", help="folder holding trace/, fetch/ and write/ of the three rocprofv3 runs (or, with --counters, of one --pmc run)")
     ap.add_argument("--workload", default="llama2_7b")
     ap.add_argument("--traffic-json", default=None, help="update this file with the measured bytes per launch")
+    ap.add_argument("--trace-only", action="store_true", help="`out` holds only trace/: print the kernel-trace tables, no traffic")
     ap.add_argument("--counters", action="store_true", help="`out` is the folder of a single rocprofv3 --pmc run: print the mean of every counter per kernel")
     a = ap.parse_args()
     if a.counters:
@@ -114,6 +115,8 @@ def main() -> int:
             "where name like '%ddp::%' group by name, grid_x order by sum(duration) desc limit 24"):
         print(f"{short(name)[:64]:64s} {grid:11d} {calls:6d} {avg:11.2f} {mn:11.2f} {mx:11.2f}")
 
+    if a.trace_only:
+        return 0
     fetch, fscale = counter_means(os.path.join(a.out, "fetch"), "FETCH_SIZE")
     write, wscale = counter_means(os.path.join(a.out, "write"), "WRITE_SIZE")
     print(f"\n== rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per dispatch, scaled by the 1 GiB calibration copy "
