@@ -287,7 +287,8 @@ int ddp_fused_sync_update_layers(ddp_ctx *ctx, int slot, int layer_first, int la
  * mean_chunk elements, then 64 slice sums per layer of the slot) in a fixed array of DDP_STATIC_SCRATCH_BYTES inside the
  * library's device image, one copy per GPU, instead of memory owned by the context.  Same arguments, same kernels and
  * bit for bit the same flat_out and layer_stats as ddp_partial_average.  Neither this call nor anything it calls
- * allocates or frees device or pinned memory; the device address of the array is resolved once per device in ddp_create.
+ * allocates or frees device or pinned memory; the device address of the array is resolved once per device in ddp_create
+ * (if that fails, the context still works and this call alone returns DDP_ESTATE with the reason).
  *   - A slot whose statistics need more than the fixed array (more than about 2^20 chunks: 2.1 G elements at the default
  *     mean_chunk) is rejected with DDP_ESHAPE before anything is launched; with layer_stats == NULL any size passes,
  *     since the scratch is then not used.

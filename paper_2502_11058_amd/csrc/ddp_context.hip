@@ -158,10 +158,10 @@ extern "C" int ddp_create(ddp_ctx **out, int device) {
     c->mean_lds = residency_pad(c, 2);
     c->copy_lds = residency_pad(c, 6);
     // the device address of the library's fixed scratch array, resolved here once per device (the device is current)
-    int rc = static_scratch_for(nullptr, device, &c->static_scratch);
-    if (rc != DDP_OK) {
-        delete c;
-        return rc;
+    // (a failure only disables ddp_partial_average_static, which then reports it; everything else works without the array)
+    if (static_scratch_for(nullptr, device, &c->static_scratch) != DDP_OK) {
+        c->static_scratch = nullptr;
+        c->static_scratch_err = g_err;
     }
     *out = c;
     return DDP_OK;

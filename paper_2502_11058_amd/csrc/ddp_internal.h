@@ -227,6 +227,7 @@ struct ddp_ctx {
     double *d_slice_sums = nullptr;  // ... followed by 64 slice sums per layer (same allocation)
     int64_t partials_cap = 0;
     double *static_scratch = nullptr;  // this device's copy of the library's fixed scratch array (ddp_partial_average_static)
+    std::string static_scratch_err;    // why it could not be resolved, if it could not
 };
 
 #endif

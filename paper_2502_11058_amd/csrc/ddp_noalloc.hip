@@ -48,7 +48,8 @@ extern "C" int ddp_partial_average_static(ddp_ctx *ctx, int slot, const float *f
                                           int local_rank, float *flat_out, double *layer_stats, void *stream) {
     return ddp::guarded(ctx, [&]() -> int {
         if (!ctx) return ddp::fail(nullptr, DDP_EINVAL, "ddp_partial_average_static: ctx is NULL");
-        if (!ctx->static_scratch) return ddp::fail(ctx, DDP_ESTATE, "ddp_partial_average_static: the fixed scratch was not resolved for this context");
+        if (!ctx->static_scratch)
+            return ddp::fail(ctx, DDP_ESTATE, "ddp_partial_average_static: the fixed scratch could not be resolved when the context was created: " + ctx->static_scratch_err);
         return ddp::partial_average_impl(ctx, "ddp_partial_average_static", false, slot, flat_local,
                                          reinterpret_cast<const void *const *>(peers), N, local_rank, flat_out, layer_stats, stream,
                                          ctx->static_scratch, (int64_t)DDP_STATIC_SCRATCH_BYTES);
