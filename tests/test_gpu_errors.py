@@ -54,6 +54,8 @@ def test_bad_arguments_are_reported_not_launched(oracle):
     _expect(1, c.ddp_local_update, opt)
     _expect(7, c.ddp_local_update, B.make_opt("adamw", 1e-3, 1))           # AdamW without state1 registered
     _expect(1, c.ddp_set_option, "no_such_option", 1)
+    _expect(1, c.ddp_set_option, "update_wg_per_cu", 33)
+    _expect(1, c.ddp_set_option, "mean_wg_per_cu", -1)
     _expect(7, c.ddp_set_option, "update_chunk", 4096)                     # after registration
     _expect(6, c.ddp_set_schedule, [0, 2], [3, 3])                         # duplicate layer in a slot
     _expect(6, c.ddp_set_schedule, [0, 1], [8])                            # layer id out of range

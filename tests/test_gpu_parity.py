@@ -464,6 +464,7 @@ def test_bf16_wire_odd_shapes(oracle, arena_offset, fused):
     {"dense_path": 0}, {"dense_path": 0, "update_chunk": 1024}, {"dense_path": 1, "update_chunk": 4096, "nontemporal": 0},
     {"dispatch_ways": 8}, {"dispatch_ways": 3, "update_chunk": 1024, "mean_chunk": 2048, "copy_chunk": 4096},
     {"update_lds": 0, "mean_lds": 0, "copy_lds": 0, "nontemporal": 0}, {"update_chunk": 1048576, "mean_chunk": 1048576, "copy_chunk": 1048576},
+    {"update_wg_per_cu": 4, "mean_wg_per_cu": 0, "copy_wg_per_cu": 1}, {"update_wg_per_cu": 32, "mean_wg_per_cu": 3, "copy_wg_per_cu": 16},
 ])
 def test_launch_options_do_not_change_results(oracle, options):
     t = run_trajectory(oracle, W.odd(n_replicas=8), options=options, arena_offset=2)
