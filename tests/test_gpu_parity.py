@@ -34,16 +34,16 @@ def _bits(a: np.ndarray) -> np.ndarray:
 
 
 def progress(msg: str) -> None:
-    """Progress line from the work itself: printed, and appended to a file the GPU machine's watchdog can see even
-    when pytest captures the output."""
+    """Progress line from the work itself: printed, and appended to the file named by DDP_TEST_PROGRESS_FILE (if set), so
+    that a long test can be followed from outside even when pytest captures the output."""
     print(msg, flush=True)
-    try:
-        d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-        os.makedirs(d, exist_ok=True)
-        with open(os.path.join(d, "test_progress.log"), "a") as f:
-            f.write(msg + "\n")
-    except OSError:
-        pass
+    path = os.environ.get("DDP_TEST_PROGRESS_FILE")
+    if path:
+        try:
+            with open(path, "a") as f:
+                f.write(msg + "\n")
+        except OSError:
+            pass
 
 
 def assert_close_fp32(got: np.ndarray, ref: np.ndarray, what: str, atol: float):
