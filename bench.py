@@ -232,9 +232,6 @@ def main() -> int:
                     help="edge of the square bf16 products of --overlap (4096: one product fills the 256 CUs)")
     ap.add_argument("--front-pad-gib", type=int, default=None, metavar="G",
                     help="leave G GiB unused at the start of the worker's slab (default 0)")
-    ap.add_argument("--placement-search", default="search", choices=["search", "hole"],
-                    help="how the second measurement picks its slab: 'search' leaves 0/16/24/32/40 GiB unused in front of the data "
-                         "inside the allocation, 'hole' allocates and frees a placeholder of that size before the slab (nothing stays unused)")
     ap.add_argument("--no-placement-search", action="store_true",
                     help="measure on the plain first allocation only.  Default for models of a billion parameters or more: measure that "
                          "first (reported as no_placement_search / value_no_placement_search), then re-allocate the slab by the "
@@ -356,7 +353,7 @@ def main() -> int:
         import gc
         gc.collect()
         torch.cuda.empty_cache()
-        rep = DeviceReplica(w, 0, options=options, policy=args.policy, wire16=args.wire16, placement_probe=args.placement_search)
+        rep = DeviceReplica(w, 0, options=options, policy=args.policy, wire16=args.wire16, placement_probe="search")
         stage_inputs(rep)
 
     if args.calibrate_copy:
@@ -541,8 +538,8 @@ def main() -> int:
         "config": {"workload": f"{w.name}: P={w.n_params}, N={w.n_replicas}, H={w.period}, {w.param_dtype} params, "
                                f"{w.optimizer}, schedule {args.policy or w.policy}, slot sizes {rep.slot_numel}",
                    "alg_bytes_per_step_avg": total_bytes / args.steps, "layer_stats": with_stats, "options": options,
-                   "placement": (f"harness placement search ({args.placement_search}): kept {rep.placement.get('kept_GiB', 0)} GiB unused in front of the "
-                                 f"data, tried {rep.placement.get('front_pad_GiB') or rep.placement.get('hole_GiB')} GiB, zero-slab probe readings "
+                   "placement": (f"harness placement search: kept {rep.placement.get('kept_GiB', 0)} GiB unused in front of the "
+                                 f"data, tried {rep.placement.get('front_pad_GiB')} GiB, zero-slab probe readings "
                                  f"{[round(x, 1) for x in rep.placement['probe_GBps']]} GB/s; the plain first allocation is in no_placement_search")
                    if first is not None else ("first allocation, no search" if args.front_pad_gib is None else f"front pad {args.front_pad_gib} GiB"),
                    "placement_kept_GiB": rep.placement.get("kept_GiB", 0) if first is not None else (args.front_pad_gib or 0)},

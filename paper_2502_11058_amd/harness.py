@@ -89,26 +89,6 @@ class DeviceReplica:
                 self._build()
                 tried.append((self._probe_step(), best_pad))
             self.placement = {"probe_GBps": [r for r, _ in tried], "front_pad_GiB": [p // GiB for _, p in tried], "kept_GiB": best_pad // GiB}
-        elif placement_probe == "hole":
-            # The same search without the cost: the slab is allocated after a throw-away allocation of G GiB that is
-            # freed again at once, so the slab sits G GiB further along in physical memory but nothing stays unused.
-            GiB = 1 << 30
-            total = torch.cuda.get_device_properties(self.dev).total_memory
-            body = self.slab.numel()
-            tried = [(self._probe_step(), 0)]
-            for hole in (16 * GiB, 24 * GiB, 32 * GiB, 40 * GiB):
-                if body + hole + 6 * GiB > total:
-                    continue
-                self._release()
-                self._build(hole=hole)
-                tried.append((self._probe_step(), hole))
-            best_rate, best_hole = max(tried)
-            if tried[-1][1] != best_hole:
-                self._release()
-                self._build(hole=best_hole)
-                tried.append((self._probe_step(), best_hole))
-            self.placement = {"probe_GBps": [r for r, _ in tried], "hole_GiB": [h // GiB for _, h in tried], "kept_hole_GiB": best_hole // GiB,
-                              "kept_GiB": 0}
         elif placement_probe:
             # Successive allocations of a slab this large alternate between two physical placements whose DRAM
             # efficiency differs by ~10 % (same kernel, same virtual layout, same TLB behaviour; the slower one
@@ -168,7 +148,7 @@ class DeviceReplica:
         torch.cuda.synchronize()
         return nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
-    def _build(self, hole: int = 0) -> None:
+    def _build(self) -> None:
         P, arena_offset, smax, n_peers, max_layers, region_skew, sp, sl, _, _ = self._regions_args
         w = self.w
         # one slab for everything this worker owns on the device; every region starts on a 2 MiB boundary
@@ -192,14 +172,7 @@ class DeviceReplica:
             place[name] = (pos + j * region_skew, nbytes, dt)
             pos += (nbytes + ALIGN - 1) // ALIGN * ALIGN
         pos += len(regions) * region_skew
-        if hole:
-            # placeholder first, slab second, placeholder freed: the slab keeps its physical place, the hole goes back to the pool
-            placeholder = torch.empty(hole, dtype=torch.uint8, device=self.dev)
-            self.slab = torch.zeros(pos, dtype=torch.uint8, device=self.dev)
-            del placeholder
-            torch.cuda.empty_cache()
-        else:
-            self.slab = torch.zeros(pos, dtype=torch.uint8, device=self.dev)
+        self.slab = torch.zeros(pos, dtype=torch.uint8, device=self.dev)
 
         def region(name):
             if name not in place:
