@@ -379,10 +379,12 @@ __device__ __forceinline__ void fused_math4(const f32x4 (&pv)[NREP - 1], typenam
 
 // Run-time replica counts (the kernels compiled for a fixed count keep all replicas in registers): a thread parks
 // each vector it loads in LDS while it forms the rank-order sum, and reads the vectors back for the statistics, so every
-// replica is fetched from memory once.  The staging area is dynamic LDS laid out [replica][thread] (each thread only
+// replica is fetched from memory once (the averaging kernel keeps the first kRegReps replicas in registers and parks only
+// the rest).  The staging area is dynamic LDS laid out [replica][thread] (each thread only
 // ever touches its own column: no barrier needed, no bank conflicts); with kStageBytes of it, stage_threads(N) threads
 // of the workgroup (whole wavefronts) take part in the vector loop.
 constexpr int kStageBytes = 65536;
+constexpr int kRegReps = 16;  // averaging kernel, run-time count: replicas of a vector that stay in registers
 inline int stage_threads(int n_replicas) {
     int t = kStageBytes / 16 / (n_replicas > 0 ? n_replicas : 1) / kWave * kWave;
     return t > kThreads ? kThreads : t;  // at least one wavefront up to DDP_MAX_REPLICAS = 64

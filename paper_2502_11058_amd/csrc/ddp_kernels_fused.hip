@@ -161,8 +161,9 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
                 store4(v, pl, av, bv);
             }
         } else {
-            // run-time replica count; with statistics the terms are parked in LDS (see stage_threads) so that the
-            // peers are fetched once, and only the first `vt` threads take part
+            // run-time replica count; with statistics the terms beyond the first kRegReps are parked in LDS (see
+            // stage_threads) so that the peers are fetched once; only the first `vt` threads take part (all of them
+            // up to 32 replicas)
             extern __shared__ __align__(16) unsigned char dyn_lds[];
             f32x4 *stage = reinterpret_cast<f32x4 *>(dyn_lds);
             const int vt = STATS ? a.stage_threads : kThreads;
@@ -176,8 +177,16 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
                 f32x4 loc = pl;
                 if constexpr (W16) loc = bf16_widen4(bf16_rne4(pl));
                 auto term = [&](int k) -> f32x4 { return k == lr ? loc : wire4<W16, NT>(a.x[k], vfo + v); };
-                f32x4 acc{};
-                for (int k0 = 0; k0 < nrep; k0 += 8) {  // eight peers in flight, then park and add them in rank order
+                // the first kRegReps terms of the rank-order sum stay in registers, the rest are parked in LDS
+                f32x4 r[kRegReps];
+#pragma unroll
+                for (int k = 0; k < kRegReps; ++k)
+                    if (k < nrep) r[k] = term(k);
+                f32x4 acc = r[0];
+#pragma unroll
+                for (int k = 1; k < kRegReps; ++k)
+                    if (k < nrep) acc = acc + r[k];
+                for (int k0 = kRegReps; k0 < nrep; k0 += 8) {  // eight more peers in flight, then park and add them in rank order
                     f32x4 x[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
@@ -185,13 +194,16 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
                         if (k0 + j < nrep) {
-                            if constexpr (STATS) stage[(k0 + j) * vt + tid] = x[j];
-                            acc = k0 + j == 0 ? x[j] : acc + x[j];
+                            if constexpr (STATS) stage[(k0 + j - kRegReps) * vt + tid] = x[j];
+                            acc = acc + x[j];
                         }
                 }
                 f32x4 m = acc * inv_n;
                 if constexpr (STATS) {
-                    for (int k = 0; k < nrep; ++k) stats4(m, stage[k * vt + tid]);
+#pragma unroll
+                    for (int k = 0; k < kRegReps; ++k)
+                        if (k < nrep) stats4(m, r[k]);
+                    for (int k = kRegReps; k < nrep; ++k) stats4(m, stage[(k - kRegReps) * vt + tid]);
                     msq4(m);
                 }
                 if constexpr (!UTS) step4(gv, m, av, bv);
@@ -216,7 +228,8 @@ template <bool A, bool G, bool M, int NR>
 static int launch_fused_n(const FusedLaunch &f, const FusedArgs &fa, void *stream) {
     const bool st = f.partials != nullptr;
     // dynamic LDS: the residency pad, or the staging area of the run-time replica count if that is larger
-    const int need = NR == 0 && st ? f.n_replicas * stage_threads(f.n_replicas) * 16 : 0;
+    const int staged = f.n_replicas > kRegReps ? f.n_replicas - kRegReps : 0;
+    const int need = NR == 0 && st ? staged * stage_threads(staged) * 16 : 0;
     const int lds = f.lds_pad > need ? f.lds_pad : need;
 #define DDP_FUSED(W, U)                                                                                \
     return st ? launch(fused_kernel<A, G, M, NR, true, W, U>, f.n_chunks, stream, lds, fa)             \
@@ -263,7 +276,7 @@ int DDP_FUSED_HALF(const FusedLaunch &f, void *stream) {
     fa.n = f.n_replicas;
     fa.local_rank = f.local_rank;
     fa.chunk_elems = f.chunk_elems;
-    fa.stage_threads = stage_threads(f.n_replicas);
+    fa.stage_threads = stage_threads(f.n_replicas > kRegReps ? f.n_replicas - kRegReps : 0);   // only the terms beyond the registers are staged
     const bool gb = f.grad_dtype == DDP_BF16, md = f.with_model;
     if (!gb && !md) return launch_fused_t<A, false, false>(f, fa, stream);
     if (!gb && md) return launch_fused_t<A, false, true>(f, fa, stream);

@@ -112,13 +112,23 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
             put4(v, m);
         }
     } else if constexpr (STATS) {
+        // Run-time replica count with statistics: the first kRegReps replicas of a vector stay in registers, the rest are
+        // parked in LDS (one column per thread), so every replica is fetched from memory once and, up to 32 replicas,
+        // every thread takes part.
         extern __shared__ __align__(16) unsigned char dyn_lds[];
         f32x4 *stage = reinterpret_cast<f32x4 *>(dyn_lds);
         const int vt = a.stage_threads;
         if (tid < vt) {
             for (int v = tid; v < nv; v += vt) {
-                f32x4 acc{};
-                for (int k0 = 0; k0 < nrep; k0 += 4) {  // four loads in flight (eight measured slower here), then park and add them in rank order
+                f32x4 r[kRegReps];
+#pragma unroll
+                for (int k = 0; k < kRegReps; ++k)
+                    if (k < nrep) r[k] = wire4<W16, NT>(a.x[k], vbase + v);
+                f32x4 acc = r[0];
+#pragma unroll
+                for (int k = 1; k < kRegReps; ++k)
+                    if (k < nrep) acc = acc + r[k];
+                for (int k0 = kRegReps; k0 < nrep; k0 += 4) {  // four more loads in flight, then park and add them in rank order
                     f32x4 x[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
@@ -126,12 +136,15 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const MeanArgs a) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         if (k0 + j < nrep) {
-                            stage[(k0 + j) * vt + tid] = x[j];
-                            acc = k0 + j == 0 ? x[j] : acc + x[j];
+                            stage[(k0 + j - kRegReps) * vt + tid] = x[j];
+                            acc = acc + x[j];
                         }
                 }
                 const f32x4 m = acc * inv_n;
-                for (int k = 0; k < nrep; ++k) stats4(m, stage[k * vt + tid]);
+#pragma unroll
+                for (int k = 0; k < kRegReps; ++k)
+                    if (k < nrep) stats4(m, r[k]);
+                for (int k = kRegReps; k < nrep; ++k) stats4(m, stage[(k - kRegReps) * vt + tid]);
                 msq4(m);
                 st<NT>(o4 + v, m);
             }
@@ -214,7 +227,8 @@ __global__ __launch_bounds__(kThreads) void stats_single_kernel(const double *__
 // Dynamic LDS of a launch: the residency pad, or the staging area of the run-time replica count if that is larger.
 template <int NREP>
 int mean_lds(const MeanLaunch &a) {
-    const int need = NREP == 0 && a.partials ? a.n_replicas * stage_threads(a.n_replicas) * 16 : 0;
+    const int staged = a.n_replicas > kRegReps ? a.n_replicas - kRegReps : 0;
+    const int need = NREP == 0 && a.partials ? staged * stage_threads(staged) * 16 : 0;
     return a.lds_pad > need ? a.lds_pad : need;
 }
 
@@ -257,7 +271,7 @@ int launch_mean(const MeanLaunch &a, void *stream) {
     ma.partials = a.partials;
     ma.inv_n = a.inv_n;
     ma.n = a.n_replicas;
-    ma.stage_threads = stage_threads(a.n_replicas);
+    ma.stage_threads = stage_threads(a.n_replicas > kRegReps ? a.n_replicas - kRegReps : 0);   // the replicas beyond the registers are staged
     int rc;
     if (a.wire16) {
         switch (a.n_replicas) {
